@@ -1,0 +1,160 @@
+/*
+ * libqsgd -- the data-parallel hot path of QSGD on one MI355X (gfx950).
+ *
+ * Alistarh, Grubic, Li, Tomioka, Vojnovic: "QSGD: Communication-Efficient SGD
+ * via Gradient Quantization and Encoding".  The three entry points are the
+ * boxed calls and the last line of Algorithm 1:
+ *
+ *   qsgd_encode             M <- Encode(g) = Code(Q_s(g))        (Alg. 1; Sec. 3.1)
+ *   qsgd_decode_accumulate  acc <- acc + sum_l Decode(M_l)       (Alg. 1; Sec. 3.1)
+ *   qsgd_sgd_step           x <- x - (eta/K) sum_l Decode(M_l)   (Alg. 1, last line)
+ *
+ * Plain C ABI: pointers and sizes only.  Every pointer named *_dev is device
+ * memory owned by the caller; everything else is host memory.  The library
+ * allocates no device memory; scratch comes in through `workspace_dev`.  All
+ * work is queued on the HIP stream passed in (a hipStream_t cast to void*,
+ * NULL = the default stream) and the calls return without waiting for it.
+ *
+ * Return value: 0, or a negative QSGD_ERR_* found on the host before anything
+ * was queued.  Conditions only the GPU can see (message capacity exceeded, a
+ * malformed message) are recorded in a status word and fetched with
+ * qsgd_message_status / qsgd_workspace_status; kernels never read or write
+ * outside the buffers described here, whatever the message bytes are.
+ */
+#ifndef QSGD_H
+#define QSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Vector code (how the tuple (||v||, sigma, zeta) of Sec. 3.1 becomes bits). */
+#define QSGD_CODE_SPARSE 0u /* Code_s : Elias(gap), sign, Elias(level) per nonzero (Sec. 3.1, App. A.2) */
+#define QSGD_CODE_DENSE  1u /* Code'_s: sign, Elias(level+1) for every coordinate (App. A.3)            */
+#define QSGD_CODE_FIXED  2u /* b-bit fields + sign bits, the "b-bit QSGD" of Sec. 5                     */
+
+/* Scale of a bucket. */
+#define QSGD_NORM_L2  0u    /* ||v||_2 (Eq. 2)                                    */
+#define QSGD_NORM_MAX 1u    /* max_i |v_i| (Sec. 4, second variation)             */
+
+#define QSGD_OK               0
+#define QSGD_ERR_INVALID_ARG (-1) /* bad parameter, null pointer, misaligned buffer        */
+#define QSGD_ERR_CAPACITY    (-2) /* message or workspace buffer too small                 */
+#define QSGD_ERR_CORRUPT     (-3) /* message does not parse / header does not match params */
+#define QSGD_ERR_HIP         (-4) /* a HIP runtime call failed                             */
+#define QSGD_ERR_UNSUPPORTED (-5) /* valid request this build has no kernel for            */
+
+#define QSGD_MAX_PEERS 64u        /* largest K                                             */
+#define QSGD_HEADER_BYTES 64u
+
+/* Parameters of one Encode, and of the messages a Decode expects.
+ *   n          length of the gradient vector (Sec. 2), 0 <= n < 2^32
+ *   d          bucket size (Sec. 4): consecutive runs of d values are quantized
+ *              independently, each with its own scale; d >= n means one bucket
+ *   seed       key of the Philox-4x32-10 generator behind the rounding draws
+ *   s          number of quantization levels (Sec. 3.1), 1 <= s <= 65535
+ *   code, norm QSGD_CODE_*, QSGD_NORM_*
+ *   stream_id  peer id and
+ *   iteration  iteration number: counter words 2 and 3 of the generator, so that
+ *              peers and iterations draw independently (element i uses word i%4 of
+ *              the block with counter (i/4 low, i/4 high, stream_id, iteration))
+ */
+typedef struct qsgd_params {
+  uint64_t n;
+  uint64_t d;
+  uint64_t seed;
+  uint32_t s;
+  uint32_t code;
+  uint32_t norm;
+  uint32_t stream_id;
+  uint32_t iteration;
+  uint32_t reserved; /* must be 0 */
+} qsgd_params;
+
+/* Library version (major*10000 + minor*100 + patch). Host only. */
+int qsgd_version(void);
+
+/* Text for a QSGD_ERR_* code. Host only; the string is static. */
+const char *qsgd_strerror(int err);
+
+/* Worst-case size in bytes of a message for these parameters (every coordinate
+ * nonzero at the top level).  A smaller buffer may be passed to qsgd_encode when
+ * the data are known to be sparse; running out is reported, never overrun.
+ * Host only.  Returns 0 for invalid parameters. */
+size_t qsgd_max_encoded_bytes(const qsgd_params *p);
+
+/* Bytes of scratch the calls below need for these parameters and up to K
+ * messages (K = 0 or 1 for encode-only use).  Host only; does not depend on the
+ * device.  Returns 0 for invalid parameters. */
+size_t qsgd_workspace_bytes(const qsgd_params *p, uint32_t K);
+
+/* Encode (Alg. 1, "M^i <- Encode(g)"; Q_s: Sec. 3.1 Eq. 2 per bucket of Sec. 4;
+ * Code_s / Code'_s: Sec. 3.1, App. A.2-A.3).
+ *   g_dev          in : n floats, device, 16-byte aligned, finite values
+ *   msg_dev        out: the message, device, 16-byte aligned, msg_capacity bytes.
+ *                  Layout: 64-byte header | table of bucket word offsets
+ *                  (Elias codes only) | bucket strings, each word aligned.
+ *                  The used length is in the header (qsgd_message_info).
+ *   workspace_dev  scratch, device, 16-byte aligned, >= qsgd_workspace_bytes(p, 1);
+ *                  contents on entry are ignored, calls sharing it must not overlap
+ *   hip_stream     the stream the kernels are queued on
+ * Errors: INVALID_ARG, CAPACITY (buffers smaller than the fixed parts), HIP,
+ * UNSUPPORTED.  Payload overflow is found on the device: the header's status
+ * becomes QSGD_ERR_CAPACITY and its length field says what was needed. */
+int qsgd_encode(const qsgd_params *p, const float *g_dev, void *msg_dev,
+                size_t msg_capacity, void *workspace_dev, size_t workspace_bytes,
+                void *hip_stream);
+
+/* Decode K messages and add them up (Alg. 1, "g^l <- Decode(M^l)" and the sum of
+ * its last line):  acc_i <- acc_i + (((0 + g^0_i) + g^1_i) + ... + g^{K-1}_i),
+ * g^l_i = ||v||_bucket * sgn_i * level_i / s  (Eq. 2), all in fp32.
+ *   msgs_dev       host array of K device pointers (16-byte aligned messages made
+ *                  with the same n, d, s, code, norm as *p), 1 <= K <= QSGD_MAX_PEERS
+ *   msg_bytes      host array of K sizes: readable bytes behind each pointer (the
+ *                  kernels never read past them, whatever a header claims)
+ *   acc_dev        in/out: n floats, device, 16-byte aligned
+ *   workspace_dev  >= qsgd_workspace_bytes(p, K); word 0 receives the status
+ * Errors: INVALID_ARG, CAPACITY, HIP, UNSUPPORTED on the host; a header that does
+ * not match *p or a string that does not parse sets the workspace status to
+ * QSGD_ERR_CORRUPT (values written for that bucket are then unspecified, nothing
+ * outside acc_dev[0..n) is touched). */
+int qsgd_decode_accumulate(const qsgd_params *p, const void *const *msgs_dev,
+                           const size_t *msg_bytes, uint32_t K, float *acc_dev,
+                           void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/* The fused receive side of Alg. 1:  x_i <- fma(-(eta/K), sum_l g^l_i, x_i) with the
+ * sum taken as in qsgd_decode_accumulate.  Arguments as there; x_dev in/out. */
+int qsgd_sgd_step(const qsgd_params *p, const void *const *msgs_dev,
+                  const size_t *msg_bytes, uint32_t K, float eta, float *x_dev,
+                  void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/* Reads a message header from a HOST copy of (at least) its first 64 bytes.
+ * Fills *out (seed is not stored: 0) and *total_bytes (either may be NULL).
+ * Returns 0, QSGD_ERR_CORRUPT (not a header), or the status the encoder left
+ * (QSGD_ERR_CAPACITY: *total_bytes is the size that would have been needed). */
+int qsgd_message_info(const void *header_host, qsgd_params *out, uint64_t *total_bytes);
+
+/* Convenience: waits for `hip_stream`, copies the header of msg_dev to the host
+ * and returns what qsgd_message_info returns (or QSGD_ERR_HIP). */
+int qsgd_message_status(const void *msg_dev, uint64_t *total_bytes, void *hip_stream);
+
+/* Waits for `hip_stream` and returns the status word the last decode call left
+ * in workspace_dev (0 or QSGD_ERR_CORRUPT), or QSGD_ERR_HIP. */
+int qsgd_workspace_status(const void *workspace_dev, void *hip_stream);
+
+/* Kernel timing for benchmarks: while enabled, every kernel launch of the
+ * library is bracketed by HIP events on its own stream.  qsgd_timing_get waits
+ * for the recorded events and reports, for kernels whose name starts with
+ * `prefix`, the summed duration in milliseconds and the launch count since the
+ * last reset.  Off by default; not for use inside stream capture. */
+int qsgd_timing_enable(int on);
+int qsgd_timing_reset(void);
+int qsgd_timing_get(const char *prefix, double *total_ms, uint64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QSGD_H */

@@ -396,8 +396,9 @@ size_t qo_max_encoded_bytes(const qo_params *p) {
   return (size_t)(4 * (H_WORDS + table_words(p) + words));
 }
 
-int qo_encode_with_draws(const qo_params *p, const float *g, const float *u_in,
-                         void *msg, size_t capacity, size_t *bytes_out) {
+static int encode_impl(const qo_params *p, const float *g, const float *u_in,
+                       uint64_t index_offset, void *msg, size_t capacity,
+                       size_t *bytes_out) {
   int rc = check_params(p);
   if (rc) return rc;
   uint64_t d = qo_bucket_size(p), nb = qo_num_buckets(p), tw = table_words(p);
@@ -416,8 +417,8 @@ int qo_encode_with_draws(const qo_params *p, const float *g, const float *u_in,
   for (uint64_t b = 0; b < nb; ++b) {
     uint64_t start = b * d, m = bucket_len(p, b);
     float norm;
-    quantize_bucket(p, g + start, m, start, u_in ? u_in + start : NULL, levels, neg,
-                    &norm, NULL, NULL);
+    quantize_bucket(p, g + start, m, index_offset + start, u_in ? u_in + start : NULL,
+                    levels, neg, &norm, NULL, NULL);
     if (tw) table[b] = (uint32_t)(bw.pos / 32);
     code_bucket(p, m, norm, levels, neg, &bw);
     bw.pos = (bw.pos + 31) & ~(uint64_t)31; /* next string starts on a word */
@@ -439,9 +440,19 @@ int qo_encode_with_draws(const qo_params *p, const float *g, const float *u_in,
   return QO_OK;
 }
 
+int qo_encode_with_draws(const qo_params *p, const float *g, const float *u_in,
+                         void *msg, size_t capacity, size_t *bytes_out) {
+  return encode_impl(p, g, u_in, 0, msg, capacity, bytes_out);
+}
+
 int qo_encode(const qo_params *p, const float *g, void *msg, size_t capacity,
               size_t *bytes_out) {
-  return qo_encode_with_draws(p, g, NULL, msg, capacity, bytes_out);
+  return encode_impl(p, g, NULL, 0, msg, capacity, bytes_out);
+}
+
+int qo_encode_slice(const qo_params *p, const float *g, uint64_t index_offset,
+                    void *msg, size_t capacity, size_t *bytes_out) {
+  return encode_impl(p, g, NULL, index_offset, msg, capacity, bytes_out);
 }
 
 int64_t qo_encode_bucket(const qo_params *p, const float *v, uint64_t m,

@@ -102,6 +102,13 @@ int qo_encode(const qo_params *p, const float *g, void *msg, size_t capacity,
 int qo_encode_with_draws(const qo_params *p, const float *g, const float *u_in,
                          void *msg, size_t capacity, size_t *bytes_out);
 
+/* Encode of a slice of a longer vector: g holds p->n elements that sit at global
+ * indices [index_offset, index_offset + n) of it, so element i takes the draw of
+ * global index index_offset + i (index_offset a multiple of the bucket size
+ * reproduces the corresponding buckets of the long vector's message). */
+int qo_encode_slice(const qo_params *p, const float *g, uint64_t index_offset,
+                    void *msg, size_t capacity, size_t *bytes_out);
+
 /* Encode ONE bucket: `v` holds its m elements, `first_index` is the global
  * index of v[0] (it selects the Philox draws), bucket geometry is not taken
  * from p->n/p->d.  Output: the bucket's string as 32-bit words.

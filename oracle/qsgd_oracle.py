@@ -90,6 +90,8 @@ def lib():
         L.qo_encode.restype = C.c_int
         L.qo_encode_with_draws.argtypes = [PP, vp, vp, vp, sz, C.POINTER(sz)]
         L.qo_encode_with_draws.restype = C.c_int
+        L.qo_encode_slice.argtypes = [PP, vp, C.c_uint64, vp, sz, C.POINTER(sz)]
+        L.qo_encode_slice.restype = C.c_int
         L.qo_encode_bucket.argtypes = [PP, vp, C.c_uint64, C.c_uint64, vp, sz]
         L.qo_encode_bucket.restype = C.c_int64
         L.qo_message_info.argtypes = [vp, sz, PP, u64p]
@@ -219,6 +221,19 @@ def encode(p: Params, g, u=None, capacity: int | None = None) -> np.ndarray:
         rc = lib().qo_encode_with_draws(C.byref(cp), _ptr(g), _ptr(u), _ptr(msg), cap,
                                         C.byref(used))
     _chk(rc, "encode")
+    return msg[: used.value // 4].copy()
+
+
+def encode_slice(p: Params, g, index_offset: int) -> np.ndarray:
+    """Message of a slice (p.n elements) of a longer vector, drawn at global indices."""
+    g = _f32(g)
+    assert g.size == p.n
+    cap = max_encoded_bytes(p)
+    msg = np.zeros((cap + 3) // 4, dtype=np.uint32)
+    used = C.c_size_t(0)
+    cp = p.c()
+    _chk(lib().qo_encode_slice(C.byref(cp), _ptr(g), index_offset, _ptr(msg), cap,
+                               C.byref(used)), "encode_slice")
     return msg[: used.value // 4].copy()
 
 

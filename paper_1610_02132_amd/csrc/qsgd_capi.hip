@@ -1,0 +1,391 @@
+// C ABI of libqsgd (see include/qsgd.h): parameter checks, geometry, kernel
+// launches.  No device memory is allocated here; scratch is the caller's.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "qsgd.h"
+#include "qsgd_device.hpp"
+#include "qsgd_kernels.hpp"
+
+namespace {
+
+using namespace qsgd;
+
+constexpr uint64_t kTotalsBytes = (uint64_t)kMaxTeams * 4;  // workspace: team totals
+constexpr uint64_t kStatusBytes = 256;                      // workspace: decode status word
+
+uint32_t omega_len_host(uint64_t k) {
+  uint32_t len = 1;
+  while (k > 1) {
+    uint32_t nb = 0;
+    for (uint64_t t = k; t; t >>= 1) ++nb;
+    len += nb;
+    k = nb - 1;
+  }
+  return len;
+}
+
+struct Geometry {
+  uint64_t n, d;       // d: effective bucket size
+  uint64_t nb;         // buckets
+  uint32_t s, code, norm;
+  uint32_t per_elem;   // worst-case bits per coordinate (Elias codes)
+  uint32_t fixed_bits;
+  uint64_t table_words;
+
+  uint64_t bucket_len(uint64_t b) const { return std::min(d, n - b * d); }
+  // Worst-case words of a bucket string of m elements.
+  uint64_t max_words(uint64_t m) const {
+    if (code == QSGD_CODE_SPARSE) return (32 + m * per_elem + 1 + 31) / 32;
+    if (code == QSGD_CODE_DENSE) return (32 + m * per_elem + 31) / 32;
+    return 2 + (m * fixed_bits + 31) / 32 + (m + 31) / 32;
+  }
+  uint64_t max_payload_words() const {
+    if (nb == 0) return 0;
+    return (nb - 1) * max_words(d) + max_words(bucket_len(nb - 1));
+  }
+  bool bucket_path() const { return n > 0 && d % 4 == 0 && d <= kMaxBucketFast; }
+};
+
+int make_geometry(const qsgd_params* p, Geometry& g) {
+  if (!p) return QSGD_ERR_INVALID_ARG;
+  if (p->s < 1 || p->s > 65535 || p->d < 1 || p->n > 0xFFFFFFFFull ||
+      p->code > QSGD_CODE_FIXED || p->norm > QSGD_NORM_MAX || p->reserved != 0)
+    return QSGD_ERR_INVALID_ARG;
+  g.n = p->n;
+  g.d = p->n == 0 ? p->d : std::min<uint64_t>(p->d, p->n);
+  g.nb = p->n == 0 ? 0 : (p->n + g.d - 1) / g.d;
+  g.s = p->s; g.code = p->code; g.norm = p->norm;
+  g.fixed_bits = fixed_field_bits(p->s, p->norm);
+  if (p->code == QSGD_CODE_SPARSE) g.per_elem = 2 + omega_len_host(p->s);
+  else if (p->code == QSGD_CODE_DENSE) g.per_elem = 1 + omega_len_host((uint64_t)p->s + 1);
+  else g.per_elem = 0;
+  g.table_words = p->code == QSGD_CODE_FIXED ? 0 : ((g.nb + 1 + 3) & ~(uint64_t)3);
+  return QSGD_OK;
+}
+
+// Team shape of the bucket path: TW wavefronts x CPW chunks of 256 cover d.
+void team_shape(uint64_t d, int& tw, int& cpw) {
+  const uint64_t chunks = (d + kChunk - 1) / kChunk;
+  if (chunks <= 1) { tw = 1; cpw = 1; }
+  else if (chunks <= 2) { tw = 1; cpw = 2; }
+  else if (chunks <= 4) { tw = 1; cpw = 4; }
+  else if (chunks <= 8) { tw = 1; cpw = 8; }
+  else if (chunks <= 16) { tw = 2; cpw = 8; }
+  else { tw = 4; cpw = 8; }
+}
+
+int device_cus() {
+  static int cus[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cus[dev] == 0) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = 256;
+    cus[dev] = v;
+  }
+  return cus[dev];
+}
+
+struct EncodePlan {
+  int tw, cpw;
+  uint32_t teams, bper;
+  uint64_t region_words;
+  uint32_t dst_words, sub_words;
+  size_t lds;
+  uint64_t ws_bytes;
+};
+
+// `teams_target` <= kMaxTeams.
+void plan_encode(const Geometry& g, uint32_t teams_target, EncodePlan& pl) {
+  team_shape(g.d, pl.tw, pl.cpw);
+  const uint32_t nb = (uint32_t)g.nb;
+  const uint32_t t = std::max(1u, std::min(nb, teams_target));
+  pl.bper = (nb + t - 1) / t;
+  pl.teams = (nb + pl.bper - 1) / pl.bper;
+  if (g.code == QSGD_CODE_FIXED) {
+    pl.region_words = 0; pl.dst_words = 2; pl.sub_words = 2;
+    pl.ws_bytes = kTotalsBytes;
+  } else {
+    pl.region_words = ((uint64_t)pl.bper * g.max_words(g.d) + 3) & ~(uint64_t)3;
+    pl.dst_words = (uint32_t)((g.max_words(g.d) + 2 + 1) & ~(uint64_t)1);
+    const uint64_t sub_bits = (uint64_t)pl.cpw * kChunk * g.per_elem;
+    pl.sub_words = (uint32_t)(((sub_bits + 31) / 32 + 2 + 1) & ~(uint64_t)1);
+    pl.ws_bytes = kTotalsBytes + (uint64_t)pl.teams * pl.region_words * 4;
+  }
+  pl.lds = 4 * ((size_t)pl.dst_words + (size_t)pl.tw * pl.sub_words) + 8 * pl.tw + 16 * pl.tw + 16;
+}
+
+// ---- optional kernel timing -----------------------------------------------------
+struct TimedLaunch { std::string name; hipEvent_t start, stop; };
+std::mutex g_timing_mu;
+bool g_timing_on = false;
+std::vector<TimedLaunch> g_launches;
+
+struct ScopedTiming {
+  hipStream_t st; bool on; TimedLaunch t;
+  ScopedTiming(const char* name, hipStream_t s) : st(s), on(false) {
+    std::lock_guard<std::mutex> lk(g_timing_mu);
+    if (!g_timing_on) return;
+    if (hipEventCreate(&t.start) != hipSuccess) return;
+    if (hipEventCreate(&t.stop) != hipSuccess) { (void)hipEventDestroy(t.start); return; }
+    t.name = name;
+    on = hipEventRecord(t.start, st) == hipSuccess;
+  }
+  ~ScopedTiming() {
+    if (!on) return;
+    (void)hipEventRecord(t.stop, st);
+    std::lock_guard<std::mutex> lk(g_timing_mu);
+    g_launches.push_back(t);
+  }
+};
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int run_decode(const qsgd_params* p, const void* const* msgs_dev, const size_t* msg_bytes,
+               uint32_t K, float c, uint32_t step, float* x_dev, void* ws, size_t ws_bytes,
+               void* hip_stream) {
+  Geometry g;
+  int rc = make_geometry(p, g);
+  if (rc) return rc;
+  if (!msgs_dev || !msg_bytes || K < 1 || K > QSGD_MAX_PEERS || !ws || !aligned16(ws))
+    return QSGD_ERR_INVALID_ARG;
+  if (g.n > 0 && (!x_dev || !aligned16(x_dev))) return QSGD_ERR_INVALID_ARG;
+  if (ws_bytes < qsgd_workspace_bytes(p, K)) return QSGD_ERR_CAPACITY;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+
+  DecodeArgs a;
+  std::memset(&a, 0, sizeof a);
+  for (uint32_t k = 0; k < K; ++k) {
+    if (!msgs_dev[k] || !aligned16(msgs_dev[k])) return QSGD_ERR_INVALID_ARG;
+    a.msgs[k] = static_cast<const uint32_t*>(msgs_dev[k]);
+    a.msg_words[k] = msg_bytes[k] / 4;
+  }
+  a.K = K; a.n = g.n; a.d = (uint32_t)g.d; a.nb = (uint32_t)g.nb; a.s = g.s; a.code = g.code;
+  a.norm_mode = g.norm; a.table_words = (uint32_t)g.table_words;
+  a.x = x_dev; a.c = c; a.step = step;
+  a.status = static_cast<uint32_t*>(ws);
+  a.fixed_bits = g.fixed_bits;
+  a.fixed_words_full = (uint32_t)g.max_words(g.d);
+
+  {
+    ScopedTiming tm("decode_check", st);
+    if (launch_decode_check(a, st) != hipSuccess) return QSGD_ERR_HIP;
+  }
+  if (g.n == 0) return QSGD_OK;
+  if (!g.bucket_path()) return QSGD_ERR_UNSUPPORTED;
+
+  const uint32_t cus = (uint32_t)device_cus();
+  if (g.code == QSGD_CODE_FIXED) {
+    const uint32_t blocks = (uint32_t)std::min<uint64_t>((g.nb + 3) / 4, (uint64_t)cus * 16);
+    ScopedTiming tm("decode_fixed", st);
+    if (launch_decode_fixed(a, blocks, st) != hipSuccess) return QSGD_ERR_HIP;
+    return QSGD_OK;
+  }
+  // Elias codes: one lane per string.
+  const uint32_t win = (uint32_t)std::min<uint64_t>((g.d + 3) & ~(uint64_t)3, 1024);
+  uint32_t gw = std::max(1u, std::min(64u / K, 4096u / win));
+  while (gw > 1 && (g.nb + gw - 1) / gw < (uint64_t)cus * 8) gw /= 2;
+  a.win = win; a.gw = gw; a.rec = std::min(16u, 64u / gw);
+  const size_t lds = 4 * ((size_t)gw * win + 64 * a.rec + 64 + 64);
+  const uint32_t blocks = (uint32_t)((g.nb + gw - 1) / gw);
+  ScopedTiming tm("decode_elias", st);
+  if (launch_decode_elias(a, blocks, lds, st) != hipSuccess) return QSGD_ERR_HIP;
+  return QSGD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int qsgd_version(void) { return 100; }
+
+const char* qsgd_strerror(int err) {
+  switch (err) {
+    case QSGD_OK: return "ok";
+    case QSGD_ERR_INVALID_ARG: return "invalid argument";
+    case QSGD_ERR_CAPACITY: return "buffer too small";
+    case QSGD_ERR_CORRUPT: return "corrupt or mismatching message";
+    case QSGD_ERR_HIP: return "HIP runtime error";
+    case QSGD_ERR_UNSUPPORTED: return "unsupported configuration";
+    default: return "unknown error";
+  }
+}
+
+size_t qsgd_max_encoded_bytes(const qsgd_params* p) {
+  Geometry g;
+  if (make_geometry(p, g)) return 0;
+  return (size_t)(4 * (H_WORDS + g.table_words + g.max_payload_words()));
+}
+
+size_t qsgd_workspace_bytes(const qsgd_params* p, uint32_t K) {
+  Geometry g;
+  if (make_geometry(p, g) || K > QSGD_MAX_PEERS) return 0;
+  uint64_t bytes = kStatusBytes + kTotalsBytes;
+  if (g.bucket_path() && g.code != QSGD_CODE_FIXED) {
+    // teams * bper < nb + teams, teams <= min(nb, kMaxTeams)
+    const uint64_t slots = g.nb + std::min<uint64_t>(g.nb, kMaxTeams);
+    bytes += slots * (g.max_words(g.d) + 4) * 4;
+  }
+  return (size_t)((bytes + 255) & ~(uint64_t)255);
+}
+
+int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t msg_capacity,
+                void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  Geometry g;
+  int rc = make_geometry(p, g);
+  if (rc) return rc;
+  if (!msg_dev || !aligned16(msg_dev) || !workspace_dev || !aligned16(workspace_dev))
+    return QSGD_ERR_INVALID_ARG;
+  if (g.n > 0 && (!g_dev || !aligned16(g_dev))) return QSGD_ERR_INVALID_ARG;
+  const uint64_t fixed_part = 4 * (H_WORDS + g.table_words);
+  if (msg_capacity < fixed_part) return QSGD_ERR_CAPACITY;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  uint32_t* header = static_cast<uint32_t*>(msg_dev);
+  uint32_t* table = g.table_words ? header + H_WORDS : nullptr;
+  uint32_t* payload = header + H_WORDS + g.table_words;
+  const uint64_t cap_words = (msg_capacity - fixed_part) / 4;
+
+  if (g.n == 0) {
+    ScopedTiming tm("encode_empty", st);
+    if (launch_write_empty(header, table, g.code, g.norm, g.s, g.d, p->stream_id, p->iteration,
+                           st) != hipSuccess)
+      return QSGD_ERR_HIP;
+    return QSGD_OK;
+  }
+  if (!g.bucket_path()) return QSGD_ERR_UNSUPPORTED;
+
+  EncodePlan pl;
+  int tw, cpw;
+  team_shape(g.d, tw, cpw);
+  const uint32_t target = std::min<uint32_t>(kMaxTeams, (uint32_t)device_cus() * (16u / tw));
+  plan_encode(g, target, pl);
+  if (workspace_bytes < kStatusBytes + pl.ws_bytes) return QSGD_ERR_CAPACITY;
+  if (g.code == QSGD_CODE_FIXED && cap_words < g.max_payload_words()) return QSGD_ERR_CAPACITY;
+
+  uint8_t* wsb = static_cast<uint8_t*>(workspace_dev) + kStatusBytes;
+  EncodeArgs a;
+  std::memset(&a, 0, sizeof a);
+  a.g = g_dev; a.n = g.n; a.d = (uint32_t)g.d; a.nb = (uint32_t)g.nb; a.s = g.s;
+  a.norm_mode = g.norm;
+  a.key0 = (uint32_t)p->seed; a.key1 = (uint32_t)(p->seed >> 32);
+  a.stream_id = p->stream_id; a.iteration = p->iteration;
+  a.bper = pl.bper; a.dst_words = pl.dst_words; a.sub_words = pl.sub_words;
+  a.header = header; a.table = table;
+  a.totals = reinterpret_cast<uint32_t*>(wsb);
+  a.staging = reinterpret_cast<uint32_t*>(wsb + kTotalsBytes);
+  a.region_words = pl.region_words;
+  a.payload = payload;
+  a.fixed_bits = g.fixed_bits;
+  a.fixed_words_full = (uint32_t)g.max_words(g.d);
+  a.fixed_payload_words = g.code == QSGD_CODE_FIXED ? g.max_payload_words() : 0;
+  {
+    ScopedTiming tm("encode_bucket", st);
+    if (launch_encode_bucket(a, g.code, pl.tw, pl.cpw, pl.teams, pl.lds, st) != hipSuccess)
+      return QSGD_ERR_HIP;
+  }
+  if (g.code != QSGD_CODE_FIXED) {
+    CompactArgs c;
+    c.staging = a.staging; c.region_words = pl.region_words; c.totals = a.totals;
+    c.table = table; c.payload = payload; c.header = header; c.cap_words = cap_words;
+    c.bper = pl.bper; c.nb = (uint32_t)g.nb; c.table_words = (uint32_t)g.table_words;
+    ScopedTiming tm("encode_compact", st);
+    if (launch_encode_compact(c, pl.teams, st) != hipSuccess) return QSGD_ERR_HIP;
+  }
+  return QSGD_OK;
+}
+
+int qsgd_decode_accumulate(const qsgd_params* p, const void* const* msgs_dev,
+                           const size_t* msg_bytes, uint32_t K, float* acc_dev,
+                           void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  return run_decode(p, msgs_dev, msg_bytes, K, 0.f, 0, acc_dev, workspace_dev, workspace_bytes,
+                    hip_stream);
+}
+
+int qsgd_sgd_step(const qsgd_params* p, const void* const* msgs_dev, const size_t* msg_bytes,
+                  uint32_t K, float eta, float* x_dev, void* workspace_dev,
+                  size_t workspace_bytes, void* hip_stream) {
+  if (K < 1) return QSGD_ERR_INVALID_ARG;
+  const float c = eta / (float)K;
+  return run_decode(p, msgs_dev, msg_bytes, K, c, 1, x_dev, workspace_dev, workspace_bytes,
+                    hip_stream);
+}
+
+int qsgd_message_info(const void* header_host, qsgd_params* out, uint64_t* total_bytes) {
+  if (!header_host) return QSGD_ERR_INVALID_ARG;
+  uint32_t h[H_WORDS];
+  std::memcpy(h, header_host, sizeof h);
+  if (h[H_MAGIC] != kMagic || h[H_VERSION] != 1) return QSGD_ERR_CORRUPT;
+  qsgd_params q;
+  std::memset(&q, 0, sizeof q);
+  q.code = h[H_CODE]; q.norm = h[H_NORM]; q.s = h[H_S];
+  q.stream_id = h[H_STREAM]; q.iteration = h[H_ITER];
+  q.d = h[H_D_LO] | ((uint64_t)h[H_D_HI] << 32);
+  q.n = h[H_N_LO] | ((uint64_t)h[H_N_HI] << 32);
+  Geometry g;
+  if (make_geometry(&q, g)) return QSGD_ERR_CORRUPT;
+  const uint64_t pw = h[H_PW_LO] | ((uint64_t)h[H_PW_HI] << 32);
+  if (out) *out = q;
+  if (total_bytes) *total_bytes = 4 * (H_WORDS + g.table_words + pw);
+  const int status = (int)h[H_STATUS];
+  if (status == 0) return QSGD_OK;
+  return status == QSGD_ERR_CAPACITY ? QSGD_ERR_CAPACITY : QSGD_ERR_CORRUPT;
+}
+
+int qsgd_message_status(const void* msg_dev, uint64_t* total_bytes, void* hip_stream) {
+  if (!msg_dev) return QSGD_ERR_INVALID_ARG;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  uint32_t h[H_WORDS];
+  if (hipStreamSynchronize(st) != hipSuccess) return QSGD_ERR_HIP;
+  if (hipMemcpy(h, msg_dev, sizeof h, hipMemcpyDeviceToHost) != hipSuccess) return QSGD_ERR_HIP;
+  return qsgd_message_info(h, nullptr, total_bytes);
+}
+
+int qsgd_workspace_status(const void* workspace_dev, void* hip_stream) {
+  if (!workspace_dev) return QSGD_ERR_INVALID_ARG;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  uint32_t w = 0;
+  if (hipStreamSynchronize(st) != hipSuccess) return QSGD_ERR_HIP;
+  if (hipMemcpy(&w, workspace_dev, sizeof w, hipMemcpyDeviceToHost) != hipSuccess)
+    return QSGD_ERR_HIP;
+  return (int)w == 0 ? QSGD_OK : QSGD_ERR_CORRUPT;
+}
+
+int qsgd_timing_enable(int on) {
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  g_timing_on = on != 0;
+  return QSGD_OK;
+}
+
+int qsgd_timing_reset(void) {
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  for (auto& t : g_launches) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+  g_launches.clear();
+  return QSGD_OK;
+}
+
+int qsgd_timing_get(const char* prefix, double* total_ms, uint64_t* launches) {
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  const std::string pre = prefix ? prefix : "";
+  double ms = 0.0;
+  uint64_t cnt = 0;
+  for (auto& t : g_launches) {
+    if (t.name.compare(0, pre.size(), pre) != 0) continue;
+    if (hipEventSynchronize(t.stop) != hipSuccess) return QSGD_ERR_HIP;
+    float e = 0.f;
+    if (hipEventElapsedTime(&e, t.start, t.stop) != hipSuccess) return QSGD_ERR_HIP;
+    ms += e;
+    ++cnt;
+  }
+  if (total_ms) *total_ms = ms;
+  if (launches) *launches = cnt;
+  return QSGD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,140 @@
+// Device-side building blocks shared by the encode and decode kernels (gfx950,
+// wave64).  Everything follows the definitions of the QSGD paper: the quantizer
+// Q_s (Sec. 3.1, Eq. 2), the recursive Elias code (App. A.2, Definition) and the
+// message layout documented in include/qsgd.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qsgd {
+
+constexpr int kWave = 64;
+constexpr int kChunk = 256;  // elements one wave covers per step: 64 lanes x float4
+
+// ---- message header (16 words) ---------------------------------------------
+constexpr uint32_t kMagic = 0x44475351u;  // 'QSGD'
+enum HeaderWord : int {
+  H_MAGIC = 0, H_VERSION, H_CODE, H_NORM, H_S, H_STREAM, H_D_LO, H_D_HI,
+  H_N_LO, H_N_HI, H_NB_LO, H_NB_HI, H_PW_LO, H_PW_HI, H_STATUS, H_ITER, H_WORDS
+};
+
+// ---- Philox-4x32-10 (Salmon et al., SC'11): the rounding draws ----------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2,
+                                              uint32_t c3, uint32_t k0, uint32_t k1,
+                                              uint32_t out[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// ---- Q_s on one coordinate (Eq. 2) ---------------------------------------------
+// t = |v| * fl(s/scale) = a*s;  l = floor(t);  p = t - l;  level = l + [u < p],
+// u = (word >> 8) * 2^-24;  t >= s (a = 1 up to rounding) gives the top level.
+__device__ __forceinline__ uint32_t quantize_one(float v, float inv, float s_f, uint32_t s,
+                                                 uint32_t word) {
+  const float t = fabsf(v) * inv;
+  const float fl = floorf(t);
+  const float p = t - fl;
+  const float u = (float)(word >> 8) * (1.0f / 16777216.0f);
+  const uint32_t z = (uint32_t)fl + ((u < p) ? 1u : 0u);
+  return (fl >= s_f) ? s : z;
+}
+
+// ---- recursive Elias code (App. A.2): a '0' at the end, binary groups in front ---
+// Returns the code word right-aligned in `code` (first bit = most significant of
+// the `len` low bits).  k >= 1, k < 2^32: len <= 43.
+__device__ __forceinline__ void omega_encode(uint32_t k, uint64_t& code, uint32_t& len) {
+  code = 0;
+  len = 1;
+  while (k > 1) {
+    const uint32_t nb = 32u - (uint32_t)__clz(k);
+    code |= (uint64_t)k << len;
+    len += nb;
+    k = nb - 1;
+  }
+}
+
+__device__ __forceinline__ uint32_t omega_length(uint32_t k) {
+  uint32_t len = 1;
+  while (k > 1) {
+    const uint32_t nb = 32u - (uint32_t)__clz(k);
+    len += nb;
+    k = nb - 1;
+  }
+  return len;
+}
+
+// ---- bit strings: stream bit j is bit 31-(j%32) of word j/32 --------------------
+// ORs the `len` (1..64) low bits of `code` into zero-initialised LDS words so that
+// the code's first bit lands on stream bit `bitoff`.
+__device__ __forceinline__ void lds_emit(uint32_t* words, uint32_t bitoff, uint64_t code,
+                                         uint32_t len) {
+  const uint64_t top = code << (64u - len);
+  const uint32_t w = bitoff >> 5, sh = bitoff & 31u;
+  const uint64_t a = top >> sh;
+  atomicOr(&words[w], (uint32_t)(a >> 32));
+  if (sh + len > 32u) atomicOr(&words[w + 1], (uint32_t)a);
+  if (sh + len > 64u) atomicOr(&words[w + 2], (uint32_t)top << (32u - sh));
+}
+
+// Same on global memory (words zero-initialised, shared by several writers).
+__device__ __forceinline__ void global_emit(uint32_t* words, uint64_t bitoff, uint64_t code,
+                                            uint32_t len) {
+  const uint64_t top = code << (64u - len);
+  const uint64_t w = bitoff >> 5;
+  const uint32_t sh = (uint32_t)(bitoff & 31u);
+  const uint64_t a = top >> sh;
+  atomicOr(&words[w], (uint32_t)(a >> 32));
+  if (sh + len > 32u) atomicOr(&words[w + 1], (uint32_t)a);
+  if (sh + len > 64u) atomicOr(&words[w + 2], (uint32_t)top << (32u - sh));
+}
+
+// ---- wavefront helpers ----------------------------------------------------------
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+__device__ __forceinline__ float wave_max_f32(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+// Inclusive prefix sum over the 64 lanes.
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int lane) {
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const uint32_t t = __shfl_up(v, o, kWave);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+__device__ __forceinline__ uint32_t lane_bcast(uint32_t v, int src) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, src);
+}
+
+// Width of the fixed-width level field: narrowest of 2/4/8/16 bits holding
+// 0..s-1 (L2 scale: level s goes to the bucket's escape word) or 0..s (max scale).
+__host__ __device__ inline uint32_t fixed_field_bits(uint32_t s, uint32_t norm_mode) {
+  const uint32_t need = norm_mode ? s + 1u : s;
+  uint32_t B = 2;
+  while (B < 16 && (1u << B) < need) B *= 2;
+  return B;
+}
+
+}  // namespace qsgd

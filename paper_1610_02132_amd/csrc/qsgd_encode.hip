@@ -1,0 +1,461 @@
+// Encode kernels: M <- Code(Q_s(g))  (Alg. 1; Q_s: Sec. 3.1 Eq. 2 per bucket of
+// Sec. 4; Code_s / Code'_s: Sec. 3.1 and App. A.2-A.3; fixed-width: Sec. 5).
+//
+// Bucket path (d <= 8192, d % 4 == 0).  A team of TW wavefronts (= one
+// workgroup) owns a contiguous run of buckets.  Per bucket: one coalesced
+// float4 read of the data into registers, the scale by a wavefront shuffle
+// reduction (fp64 accumulation), one Philox block per float4, stochastic
+// rounding, code lengths, a wavefront prefix sum for bit offsets, and the code
+// words OR-ed into an LDS image of the bucket's string.  Strings have
+// data-dependent lengths, so a team appends them to its own region of the
+// workspace and a second, small kernel moves the regions to their final place
+// (exclusive sum over at most a few thousand team totals): no team ever waits
+// for another one.  Fixed-width strings have closed-form offsets and go straight
+// to the message.
+#include "qsgd_device.hpp"
+#include "qsgd_kernels.hpp"
+
+namespace qsgd {
+
+namespace {
+
+// Per-wave summary of the records it produced for the current bucket.
+struct WaveInfo {
+  uint32_t first_pos;  // 1-based position of its first nonzero (0: none)
+  uint32_t last_pos;   // 1-based position of its last nonzero
+  uint32_t bits;       // bits in its sub-stream (first record's gap left out)
+};
+
+template <int TW>
+__device__ __forceinline__ void team_sync() {
+  __syncthreads();  // one wavefront per team: only orders the LDS traffic
+}
+
+// Loads the float4 of this lane for the chunk starting `eoff` elements into the
+// bucket; elements at or past m read as 0.
+__device__ __forceinline__ float4 load_quad(const float* __restrict__ gb, uint32_t eoff,
+                                            uint32_t m) {
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (eoff + 3 < m) {
+    v = *reinterpret_cast<const float4*>(gb + eoff);
+  } else {
+    if (eoff + 0 < m) v.x = gb[eoff + 0];
+    if (eoff + 1 < m) v.y = gb[eoff + 1];
+    if (eoff + 2 < m) v.z = gb[eoff + 2];
+  }
+  return v;
+}
+
+}  // namespace
+
+// TW wavefronts per bucket, each holding up to CPW chunks of 256 elements.
+template <int TW, int CPW, int CODE>
+__global__ __launch_bounds__(64 * TW) void k_encode_bucket(EncodeArgs a) {
+  extern __shared__ uint32_t smem[];
+  // LDS: [dst image of the bucket string][TW sub-streams][reduction scratch]
+  uint32_t* const dst = smem;
+  uint32_t* const sub_all = smem + a.dst_words;
+  double* const red = reinterpret_cast<double*>(smem + a.dst_words + TW * a.sub_words);
+  WaveInfo* const winfo = reinterpret_cast<WaveInfo*>(red + TW);
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  uint32_t* const sub = sub_all + wave * a.sub_words;
+
+  for (uint32_t j = tid; j < a.dst_words + TW * a.sub_words; j += 64 * TW) smem[j] = 0;
+
+  if (blockIdx.x == 0 && tid == 0) {  // header; length and status are completed later
+    uint32_t* h = a.header;
+    h[H_MAGIC] = kMagic; h[H_VERSION] = 1; h[H_CODE] = CODE; h[H_NORM] = a.norm_mode;
+    h[H_S] = a.s; h[H_STREAM] = a.stream_id;
+    h[H_D_LO] = (uint32_t)a.d; h[H_D_HI] = 0;
+    h[H_N_LO] = (uint32_t)a.n; h[H_N_HI] = (uint32_t)(a.n >> 32);
+    h[H_NB_LO] = a.nb; h[H_NB_HI] = 0;
+    h[H_PW_LO] = (uint32_t)a.fixed_payload_words;
+    h[H_PW_HI] = (uint32_t)(a.fixed_payload_words >> 32);
+    h[H_STATUS] = 0; h[H_ITER] = a.iteration;
+  }
+  __syncthreads();
+
+  const uint32_t b_begin = blockIdx.x * a.bper;
+  const uint32_t b_end = min(b_begin + a.bper, a.nb);
+  uint32_t* const region = a.staging + (uint64_t)blockIdx.x * a.region_words;
+  uint32_t run = 0;  // words this team has appended to its region
+
+  const uint32_t s = a.s;
+  const float s_f = (float)s;
+
+  for (uint32_t b = b_begin; b < b_end; ++b) {
+    const uint64_t base = (uint64_t)b * a.d;
+    const uint32_t m = (uint32_t)min((uint64_t)a.d, a.n - base);
+    const float* __restrict__ gb = a.g + base;
+
+    // ---- read the bucket once, accumulate the scale --------------------------
+    float4 v[CPW];
+    double ss = 0.0;
+    float mx = 0.f;
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+      const uint32_t cstart = (uint32_t)(wave * CPW + c) * kChunk;
+      v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (cstart < m) v[c] = load_quad(gb, cstart + lane * 4, m);
+    }
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+      if (a.norm_mode == 0) {
+        ss += (double)v[c].x * (double)v[c].x;
+        ss += (double)v[c].y * (double)v[c].y;
+        ss += (double)v[c].z * (double)v[c].z;
+        ss += (double)v[c].w * (double)v[c].w;
+      } else {
+        mx = fmaxf(fmaxf(mx, fmaxf(fabsf(v[c].x), fabsf(v[c].y))),
+                   fmaxf(fabsf(v[c].z), fabsf(v[c].w)));
+      }
+    }
+    float scale;
+    if (a.norm_mode == 0) {
+      ss = wave_sum_f64(ss);
+      if (TW > 1) {
+        if (lane == 0) red[wave] = ss;
+        __syncthreads();
+        ss = 0.0;
+#pragma unroll
+        for (int w = 0; w < TW; ++w) ss += red[w];
+      }
+      scale = (float)sqrt(ss);
+    } else {
+      mx = wave_max_f32(mx);
+      if (TW > 1) {
+        if (lane == 0) red[wave] = (double)mx;
+        __syncthreads();
+        mx = 0.f;
+#pragma unroll
+        for (int w = 0; w < TW; ++w) mx = fmaxf(mx, (float)red[w]);
+      }
+      scale = mx;
+    }
+    const float inv = (scale > 0.f) ? s_f / scale : 0.f;
+
+    // ---- fixed width: closed-form placement, straight to the message ---------
+    if (CODE == QSGD_CODE_FIXED) {
+      const uint32_t B = a.fixed_bits;
+      const uint32_t fmax = (1u << B) - 1u;
+      uint32_t* const str = a.payload + (uint64_t)b * a.fixed_words_full;
+      const uint32_t lw = (m * B + 31u) >> 5, sw = (m + 31u) >> 5;
+      uint32_t* const lplane = str + 2;
+      uint32_t* const splane = lplane + lw;
+      uint32_t esc = 0xFFFFFFFFu;
+#pragma unroll
+      for (int c = 0; c < CPW; ++c) {
+        const uint32_t cstart = (uint32_t)(wave * CPW + c) * kChunk;
+        if (cstart >= m) continue;
+        const uint32_t e0 = cstart + lane * 4;
+        const uint64_t q = (base + e0) >> 2;
+        uint32_t r[4];
+        philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.stream_id, a.iteration, a.key0,
+                      a.key1, r);
+        uint32_t z[4];
+        z[0] = quantize_one(v[c].x, inv, s_f, s, r[0]);
+        z[1] = quantize_one(v[c].y, inv, s_f, s, r[1]);
+        z[2] = quantize_one(v[c].z, inv, s_f, s, r[2]);
+        z[3] = quantize_one(v[c].w, inv, s_f, s, r[3]);
+        const uint32_t nib = (v[c].x < 0.f ? 1u : 0u) | (v[c].y < 0.f ? 2u : 0u) |
+                             (v[c].z < 0.f ? 4u : 0u) | (v[c].w < 0.f ? 8u : 0u);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (z[j] > fmax) { esc = e0 + j; z[j] = fmax; }
+        // level plane: element i's field at bit i*B (LSB first)
+        if (B == 8) {
+          const uint32_t w = z[0] | (z[1] << 8) | (z[2] << 16) | (z[3] << 24);
+          const uint32_t wi = e0 >> 2;
+          if (wi < lw) lplane[wi] = w;
+        } else if (B == 16) {
+          const uint32_t wi = e0 >> 1;
+          if (wi < lw) lplane[wi] = z[0] | (z[1] << 16);
+          if (wi + 1 < lw) lplane[wi + 1] = z[2] | (z[3] << 16);
+        } else if (B == 4) {
+          uint32_t h = z[0] | (z[1] << 4) | (z[2] << 8) | (z[3] << 12);
+          h |= __shfl_down(h, 1, kWave) << 16;
+          const uint32_t wi = e0 >> 3;
+          if ((lane & 1) == 0 && wi < lw) lplane[wi] = h;
+        } else {  // B == 2
+          uint32_t h = z[0] | (z[1] << 2) | (z[2] << 4) | (z[3] << 6);
+          h |= __shfl_down(h, 1, kWave) << 8;
+          h |= __shfl_down(h, 2, kWave) << 16;
+          const uint32_t wi = e0 >> 4;
+          if ((lane & 3) == 0 && wi < lw) lplane[wi] = h;
+        }
+        // sign plane: element i at bit i%32 of word i/32
+        uint32_t sg = nib;
+        sg |= __shfl_down(sg, 1, kWave) << 4;
+        sg |= __shfl_down(sg, 2, kWave) << 8;
+        sg |= __shfl_down(sg, 4, kWave) << 16;
+        const uint32_t si = e0 >> 5;
+        if ((lane & 7) == 0 && si < sw) splane[si] = sg;
+      }
+      // escape word: at most one lane of the team holds an index
+      const uint64_t eb = __ballot(esc != 0xFFFFFFFFu);
+      if (TW == 1) {
+        if (eb) esc = lane_bcast(esc, __ffsll((unsigned long long)eb) - 1);
+        if (lane == 0) { str[0] = __float_as_uint(scale); str[1] = esc; }
+      } else {
+        if (tid == 0) winfo[0].first_pos = 0xFFFFFFFFu;
+        __syncthreads();
+        if (esc != 0xFFFFFFFFu) winfo[0].first_pos = esc;
+        __syncthreads();
+        if (tid == 0) { str[0] = __float_as_uint(scale); str[1] = winfo[0].first_pos; }
+        __syncthreads();
+      }
+      continue;
+    }
+
+    // ---- Elias codes: each wave builds its sub-stream in LDS -----------------
+    uint32_t wbits = 0;      // bits in this wave's sub-stream so far
+    uint32_t first_pos = 0;  // 1-based position of the wave's first nonzero
+    uint32_t carry = 0;      // 1-based position of the latest nonzero so far
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+      const uint32_t cstart = (uint32_t)(wave * CPW + c) * kChunk;
+      if (cstart >= m) continue;
+      const uint32_t e0 = cstart + lane * 4;
+      const uint64_t q = (base + e0) >> 2;
+      uint32_t r[4];
+      philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.stream_id, a.iteration, a.key0,
+                    a.key1, r);
+      uint32_t z[4];
+      z[0] = quantize_one(v[c].x, inv, s_f, s, r[0]);
+      z[1] = quantize_one(v[c].y, inv, s_f, s, r[1]);
+      z[2] = quantize_one(v[c].z, inv, s_f, s, r[2]);
+      z[3] = quantize_one(v[c].w, inv, s_f, s, r[3]);
+      const uint32_t neg[4] = {v[c].x < 0.f ? 1u : 0u, v[c].y < 0.f ? 1u : 0u,
+                               v[c].z < 0.f ? 1u : 0u, v[c].w < 0.f ? 1u : 0u};
+      uint64_t code[4];
+      uint32_t len[4] = {0, 0, 0, 0};
+
+      if (CODE == QSGD_CODE_DENSE) {
+        // Code'_s: sign bit, Elias(level + 1), for every coordinate below m.
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (e0 + j < m) {
+            uint64_t lc; uint32_t ll;
+            omega_encode(z[j] + 1u, lc, ll);
+            code[j] = ((uint64_t)neg[j] << ll) | lc;
+            len[j] = ll + 1u;
+          }
+        }
+      } else {
+        // Code_s: Elias(gap), sign bit, Elias(level) per nonzero.  The gap of the
+        // wave's very first nonzero is left out here and added when the team's
+        // sub-streams are joined (it depends on the waves before this one).
+        const uint32_t nzm = (z[0] ? 1u : 0u) | (z[1] ? 2u : 0u) | (z[2] ? 4u : 0u) |
+                             (z[3] ? 8u : 0u);
+        const uint64_t anyb = __ballot(nzm != 0);
+        if (anyb == 0) continue;  // whole chunk quantized to zero
+        const uint32_t hi = nzm ? 31u - (uint32_t)__clz(nzm) : 0u;
+        const uint64_t hb0 = __ballot(nzm && (hi & 1u));
+        const uint64_t hb1 = __ballot(nzm && (hi & 2u));
+        const uint64_t below = anyb & ((1ull << lane) - 1ull);
+        uint32_t prev = carry;
+        if (below) {
+          const int P = 63 - __clzll((long long)below);
+          prev = cstart + 4u * P + (uint32_t)((hb0 >> P) & 1ull) +
+                 2u * (uint32_t)((hb1 >> P) & 1ull) + 1u;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (z[j]) {
+            const uint32_t pos = e0 + j + 1u;
+            uint64_t lc; uint32_t ll;
+            omega_encode(z[j], lc, ll);
+            uint64_t cw = ((uint64_t)neg[j] << ll) | lc;
+            uint32_t cl = ll + 1u;
+            if (prev != 0) {
+              uint64_t gc; uint32_t gl;
+              omega_encode(pos - prev, gc, gl);
+              cw |= gc << cl;
+              cl += gl;
+            }
+            code[j] = cw;
+            len[j] = cl;
+            prev = pos;
+          }
+        }
+        const int F = __ffsll((unsigned long long)anyb) - 1;
+        const int L = 63 - __clzll((long long)anyb);
+        if (first_pos == 0)
+          first_pos = cstart + 4u * F + (uint32_t)(__ffs((int)lane_bcast(nzm, F)) - 1) + 1u;
+        carry = cstart + 4u * L + (31u - (uint32_t)__clz(lane_bcast(nzm, L))) + 1u;
+      }
+
+      const uint32_t tot = len[0] + len[1] + len[2] + len[3];
+      const uint32_t incl = wave_incl_scan_u32(tot, lane);
+      uint32_t off = wbits + incl - tot;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (len[j]) {
+          lds_emit(sub, off, code[j], len[j]);
+          off += len[j];
+        }
+      }
+      wbits += lane_bcast(incl, 63);
+    }
+
+    // ---- join the sub-streams into the bucket string --------------------------
+    if (lane == 0) {
+      winfo[wave].first_pos = first_pos;
+      winfo[wave].last_pos = carry;
+      winfo[wave].bits = wbits;
+    }
+    __syncthreads();
+    uint32_t cursor = 32;  // after the scale
+    uint32_t my_start = 0, my_glen = 0, my_gap = 0;
+    {
+      uint32_t prev_last = 0;
+#pragma unroll
+      for (int w = 0; w < TW; ++w) {
+        const WaveInfo wi = winfo[w];
+        uint32_t glen = 0, gap = 0;
+        if (CODE == QSGD_CODE_SPARSE && wi.first_pos) {
+          gap = wi.first_pos - prev_last;
+          glen = omega_length(gap);
+          prev_last = wi.last_pos;
+        }
+        if (w == wave) { my_start = cursor; my_glen = glen; my_gap = gap; }
+        cursor += glen + wi.bits;
+      }
+    }
+    const uint32_t stop = (CODE == QSGD_CODE_SPARSE) ? 1u : 0u;
+    const uint32_t words = (cursor + stop + 31u) >> 5;
+    if (tid == 0) {
+      dst[0] = __float_as_uint(scale);
+      if (stop) lds_emit(dst, cursor, 1ull, 1u);
+    }
+    if (lane == 0 && my_glen) {
+      uint64_t gc; uint32_t gl;
+      omega_encode(my_gap, gc, gl);
+      lds_emit(dst, my_start, gc, gl);
+    }
+    {
+      const uint32_t o = my_start + my_glen;
+      const uint32_t w0 = o >> 5, sh = o & 31u;
+      const uint32_t nsub = (wbits + 31u) >> 5;
+      for (uint32_t j = lane; j < nsub; j += kWave) {
+        const uint32_t x = sub[j];
+        sub[j] = 0;
+        if (x) {
+          atomicOr(&dst[w0 + j], x >> sh);
+          if (sh) atomicOr(&dst[w0 + j + 1], x << (32u - sh));
+        }
+      }
+    }
+    __syncthreads();
+
+    // ---- append the string to the team's region --------------------------------
+    if (tid == 0) a.table[b] = run;  // relative to the region; rebased later
+    for (uint32_t j = tid; j < words; j += 64 * TW) {
+      region[run + j] = dst[j];
+      dst[j] = 0;
+    }
+    run += words;
+    __syncthreads();
+  }
+  if (CODE != QSGD_CODE_FIXED && tid == 0) a.totals[blockIdx.x] = run;
+}
+
+// Moves each team's region to its place in the message: base_j = sum of the
+// totals of the teams before j.  One workgroup per team.
+__global__ __launch_bounds__(256) void k_encode_compact(CompactArgs a) {
+  __shared__ unsigned long long part[4];
+  const int tid = threadIdx.x;
+  const uint32_t j = blockIdx.x;
+  unsigned long long acc = 0;
+  for (uint32_t i = tid; i < j; i += 256) acc += a.totals[i];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, kWave);
+  if ((tid & 63) == 0) part[tid >> 6] = acc;
+  __syncthreads();
+  const uint64_t base = part[0] + part[1] + part[2] + part[3];
+  const uint32_t mine = a.totals[j];
+  const uint32_t b_begin = j * a.bper;
+  const uint32_t b_end = min(b_begin + a.bper, a.nb);
+  const bool fits = base + mine <= a.cap_words && base + mine <= 0xFFFFFFFFull;
+  if (fits) {
+    const uint32_t* __restrict__ src = a.staging + (uint64_t)j * a.region_words;
+    uint32_t* __restrict__ dstp = a.payload + base;
+    for (uint32_t i = tid; i < mine; i += 256) dstp[i] = src[i];
+  }
+  for (uint32_t b = b_begin + tid; b < b_end; b += 256)
+    a.table[b] = (uint32_t)min(base + a.table[b], (uint64_t)0xFFFFFFFFull);
+  if (tid == 0) {
+    if (!fits) atomicExch(&a.header[H_STATUS], (uint32_t)QSGD_ERR_CAPACITY);
+    if (j == gridDim.x - 1) {
+      const uint64_t total = base + mine;
+      a.table[a.nb] = (uint32_t)min(total, (uint64_t)0xFFFFFFFFull);
+      for (uint32_t i = a.nb + 1; i < a.table_words; ++i) a.table[i] = 0;  // padding
+      a.header[H_PW_LO] = (uint32_t)total;
+      a.header[H_PW_HI] = (uint32_t)(total >> 32);
+    }
+  }
+}
+
+// Header of an empty message (n = 0).
+__global__ void k_write_empty(uint32_t* header, uint32_t* table, uint32_t code, uint32_t norm,
+                              uint32_t s, uint64_t d, uint32_t stream_id, uint32_t iteration) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    header[H_MAGIC] = kMagic; header[H_VERSION] = 1; header[H_CODE] = code;
+    header[H_NORM] = norm; header[H_S] = s; header[H_STREAM] = stream_id;
+    header[H_D_LO] = (uint32_t)d; header[H_D_HI] = (uint32_t)(d >> 32);
+    header[H_N_LO] = 0; header[H_N_HI] = 0; header[H_NB_LO] = 0; header[H_NB_HI] = 0;
+    header[H_PW_LO] = 0; header[H_PW_HI] = 0; header[H_STATUS] = 0;
+    header[H_ITER] = iteration;
+    if (table) { table[0] = 0; table[1] = 0; table[2] = 0; table[3] = 0; }
+  }
+}
+
+// ---- launch table -------------------------------------------------------------
+template <int TW, int CPW>
+static hipError_t launch_tw_cpw(const EncodeArgs& a, uint32_t code, dim3 grid, size_t lds,
+                                hipStream_t st) {
+  switch (code) {
+    case QSGD_CODE_SPARSE:
+      hipLaunchKernelGGL((k_encode_bucket<TW, CPW, QSGD_CODE_SPARSE>), grid, dim3(64 * TW), lds,
+                         st, a);
+      break;
+    case QSGD_CODE_DENSE:
+      hipLaunchKernelGGL((k_encode_bucket<TW, CPW, QSGD_CODE_DENSE>), grid, dim3(64 * TW), lds,
+                         st, a);
+      break;
+    default:
+      hipLaunchKernelGGL((k_encode_bucket<TW, CPW, QSGD_CODE_FIXED>), grid, dim3(64 * TW), lds,
+                         st, a);
+      break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_encode_bucket(const EncodeArgs& a, uint32_t code, int tw, int cpw,
+                                uint32_t teams, size_t lds, hipStream_t st) {
+  const dim3 grid(teams);
+  if (tw == 1 && cpw == 1) return launch_tw_cpw<1, 1>(a, code, grid, lds, st);
+  if (tw == 1 && cpw == 2) return launch_tw_cpw<1, 2>(a, code, grid, lds, st);
+  if (tw == 1 && cpw == 4) return launch_tw_cpw<1, 4>(a, code, grid, lds, st);
+  if (tw == 1 && cpw == 8) return launch_tw_cpw<1, 8>(a, code, grid, lds, st);
+  if (tw == 2 && cpw == 8) return launch_tw_cpw<2, 8>(a, code, grid, lds, st);
+  if (tw == 4 && cpw == 8) return launch_tw_cpw<4, 8>(a, code, grid, lds, st);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_encode_compact(const CompactArgs& a, uint32_t teams, hipStream_t st) {
+  hipLaunchKernelGGL(k_encode_compact, dim3(teams), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_write_empty(uint32_t* header, uint32_t* table, uint32_t code, uint32_t norm,
+                              uint32_t s, uint64_t d, uint32_t stream_id, uint32_t iteration,
+                              hipStream_t st) {
+  hipLaunchKernelGGL(k_write_empty, dim3(1), dim3(64), 0, st, header, table, code, norm, s, d,
+                     stream_id, iteration);
+  return hipGetLastError();
+}
+
+}  // namespace qsgd

@@ -1,0 +1,86 @@
+// Argument blocks and launchers of the HIP kernels (internal to libqsgd).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qsgd.h"
+
+namespace qsgd {
+
+constexpr uint32_t kMaxBucketFast = 8192;  // largest bucket the register path holds
+constexpr uint32_t kMaxTeams = 8192;       // most teams (regions) one encode uses
+
+struct EncodeArgs {
+  const float* g;
+  uint64_t n;
+  uint32_t d;           // bucket size (<= kMaxBucketFast on this path)
+  uint32_t nb;          // number of buckets
+  uint32_t s;
+  uint32_t norm_mode;
+  uint32_t key0, key1;  // Philox key (seed low, high)
+  uint32_t stream_id, iteration;
+  uint32_t bper;        // buckets per team
+  uint32_t dst_words;   // LDS words of the bucket-string image (even)
+  uint32_t sub_words;   // LDS words of one wave's sub-stream (even)
+  uint32_t* header;     // message header (16 words)
+  uint32_t* table;      // nb+1 word offsets (Elias codes)
+  uint32_t* staging;    // workspace: one region per team
+  uint64_t region_words;
+  uint32_t* totals;     // workspace: words appended by each team
+  // fixed width only
+  uint32_t* payload;
+  uint32_t fixed_bits;
+  uint32_t fixed_words_full;  // words of a full bucket's string
+  uint64_t fixed_payload_words;
+};
+
+struct CompactArgs {
+  const uint32_t* staging;
+  uint64_t region_words;
+  const uint32_t* totals;
+  uint32_t* table;
+  uint32_t* payload;
+  uint32_t* header;
+  uint64_t cap_words;  // payload words the message buffer can hold
+  uint32_t bper;
+  uint32_t nb;
+  uint32_t table_words;  // padded table length
+};
+
+struct DecodeArgs {
+  const uint32_t* msgs[QSGD_MAX_PEERS];
+  uint64_t msg_words[QSGD_MAX_PEERS];  // readable words behind each pointer
+  uint32_t K;
+  uint64_t n;
+  uint32_t d;
+  uint32_t nb;
+  uint32_t s;
+  uint32_t code;
+  uint32_t norm_mode;
+  uint32_t table_words;  // padded table length in words (0 for fixed width)
+  float* x;              // acc (accumulate) or x (step)
+  float c;               // eta / K (step)
+  uint32_t step;         // 1: x <- fma(-c, sum, x); 0: x <- x + sum
+  uint32_t* status;      // workspace word 0
+  // Elias path geometry
+  uint32_t gw;           // buckets per wavefront
+  uint32_t win;          // window (positions per bucket per pass), multiple of 4
+  uint32_t rec;          // record slots per string per round
+  // fixed width
+  uint32_t fixed_bits;
+  uint32_t fixed_words_full;
+};
+
+hipError_t launch_encode_bucket(const EncodeArgs& a, uint32_t code, int tw, int cpw,
+                                uint32_t teams, size_t lds, hipStream_t st);
+hipError_t launch_encode_compact(const CompactArgs& a, uint32_t teams, hipStream_t st);
+hipError_t launch_write_empty(uint32_t* header, uint32_t* table, uint32_t code, uint32_t norm,
+                              uint32_t s, uint64_t d, uint32_t stream_id, uint32_t iteration,
+                              hipStream_t st);
+
+hipError_t launch_decode_check(const DecodeArgs& a, hipStream_t st);
+hipError_t launch_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t st);
+hipError_t launch_decode_elias(const DecodeArgs& a, uint32_t blocks, size_t lds, hipStream_t st);
+
+}  // namespace qsgd
