@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Throughput of the QSGD hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic gradients that
+are already resident in HBM: K x qsgd_encode (one message per peer) followed by
+one qsgd_sgd_step that decodes the K messages, sums them and updates x.
+`value` = fp32 gradient bytes through the path per second = 4*K*n*steps / time.
+
+Prints ONE JSON line (see the keys below); everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, vendor figure
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c5", help="c1..c5 (default c5: n=1e9, s=4, d=8192, K=16)")
+    ap.add_argument("--n", type=int, default=0, help="shrink the workload to n elements (debug)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0,
+                    help="target CPU time of the oracle baseline sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build measures one GPU only (the K peers' messages are K buffers "
+            "resident on it); --gpus must be 1")
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_1610_02132_amd as q
+    from paper_1610_02132_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 2
+    torch.cuda.set_device(0)
+    w = W.WORKLOADS[args.workload]
+    if args.n:
+        w = W.scaled(w, args.n)
+    K, n = w.K, w.n
+    log(f"workload {w.name}: n={n} s={w.s} d={w.d} code={w.code} K={K} ({w.note})")
+
+    def params(k):
+        return q.Params(n=n, s=w.s, d=w.d, code=w.code, seed=w.seed, stream_id=k, iteration=0)
+
+    # ---- inputs, resident in HBM ------------------------------------------------
+    t0 = time.time()
+    grads = [W.gradient(w, k, device="cuda") for k in range(K)]
+    x = W.parameters(w, device="cuda")
+    torch.cuda.synchronize()
+    log(f"inputs generated in {time.time() - t0:.1f}s "
+        f"({(K + 1) * 4 * n / 2**30:.1f} GiB resident)")
+
+    ws = torch.empty(q.qsgd_workspace_bytes(params(0), K) // 4, dtype=torch.int32, device="cuda")
+    # size the message buffers from a first encode into a worst-case buffer
+    cap_max = q.qsgd_max_encoded_bytes(params(0))
+    probe = torch.empty(cap_max // 4, dtype=torch.int32, device="cuda")
+    q.qsgd_encode(params(0), grads[0], probe, ws)
+    status, total0 = q.qsgd_message_status(probe)
+    assert status == 0, status
+    del probe
+    cap = min(cap_max, (int(total0 * 1.25) + 4096) & ~255)
+    msgs = [torch.empty(cap // 4, dtype=torch.int32, device="cuda") for _ in range(K)]
+    log(f"message: {total0} bytes = {8 * total0 / n:.3f} bits/element; capacity {cap} bytes each")
+
+    def one_step():
+        for k in range(K):
+            q.qsgd_encode(params(k), grads[k], msgs[k], ws)
+        q.qsgd_sgd_step(params(0), msgs, w.eta, x, ws)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    sizes = []
+    for k in range(K):
+        st, tot = q.qsgd_message_status(msgs[k])
+        assert st == 0, (k, st)
+        sizes.append(tot)
+    assert q.qsgd_workspace_status(ws) == 0
+    msg_bytes_avg = float(np.mean(sizes))
+
+    # ---- timed region: exactly --steps steps ---------------------------------------
+    q.qsgd_timing_reset()
+    q.qsgd_timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    q.qsgd_timing_enable(False)
+    assert q.qsgd_workspace_status(ws) == 0
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = 4.0 * K * n * args.steps / elapsed / 1e9
+
+    kern = {}
+    for name in ("encode_bucket", "encode_compact", "encode_general", "decode_check",
+                 "decode_fixed", "decode_elias", "decode_general"):
+        ms, cnt = q.qsgd_timing_get(name)
+        if cnt:
+            kern[name] = {"ms_total": ms, "launches": cnt, "ms_avg": ms / cnt}
+    q.qsgd_timing_reset()
+    enc_ms = sum(v["ms_total"] for k_, v in kern.items() if k_.startswith("encode")) / (args.steps * K)
+    dec_ms = sum(v["ms_total"] for k_, v in kern.items() if k_.startswith("decode")) / args.steps
+    enc_gbps = 4.0 * n / (enc_ms * 1e-3) / 1e9
+    dec_gbps = 4.0 * K * n / (dec_ms * 1e-3) / 1e9
+
+    # ---- roofline of the dominant kernel (HBM bound: a streaming codec) ---------------
+    nb = (n + min(w.d, n) - 1) // min(w.d, n)
+    table_bytes = 0 if w.code == W.CODE_FIXED else 4 * (nb + 1)
+    enc_alg = 4.0 * n + msg_bytes_avg                       # read g once, write the message once
+    dec_alg = K * msg_bytes_avg + 8.0 * n                   # read K messages, read + write x
+    enc_main = "encode_bucket" if "encode_bucket" in kern else "encode_general"
+    dec_main = next((k_ for k_ in ("decode_elias", "decode_fixed", "decode_general") if k_ in kern), None)
+    enc_total = kern[enc_main]["ms_total"]
+    dec_total = kern[dec_main]["ms_total"] if dec_main else 0.0
+    if enc_total >= dec_total:
+        dom, dom_alg = enc_main, enc_alg
+    else:
+        dom, dom_alg = dec_main, dec_alg
+    achieved = dom_alg / (kern[dom]["ms_avg"] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": None, "bytes_per_launch": dom_alg,
+                "avg_launch_ms": round(kern[dom]["ms_avg"], 4)}
+    other, other_alg = (dec_main, dec_alg) if dom == enc_main else (enc_main, enc_alg)
+    roofline_other = None
+    if other:
+        a2 = other_alg / (kern[other]["ms_avg"] * 1e-3) / 1e9
+        roofline_other = {"bound": "hbm", "kernel": other, "achieved": round(a2, 1),
+                          "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                          "frac": round(a2 / HBM_PEAK_GBPS, 4), "bytes_per_launch": other_alg,
+                          "avg_launch_ms": round(kern[other]["ms_avg"], 4)}
+
+    # ---- plain copy ceiling of this machine, for context -------------------------------------
+    src = grads[0]
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 8.0 * n / (time.perf_counter() - t0) / 1e9
+    del dst
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload ------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import qsgd_oracle as qo
+        d_eff = min(w.d, n)
+
+        def run_oracle(ns):
+            ns = max(d_eff, ns - ns % d_eff) if ns < n else n
+            ws_ = W.scaled(w, ns) if ns < n else w
+            gs = [grads[k][:ns].cpu().numpy() for k in range(K)]
+            xs = x[:ns].cpu().numpy()
+            t0 = time.perf_counter()
+            ms_ = [qo.encode(qo.Params(n=ns, s=w.s, d=ws_.d, code=w.code, seed=w.seed,
+                                       stream_id=k), gs[k]) for k in range(K)]
+            qo.sgd_step(ms_, w.eta, xs)
+            return ns, time.perf_counter() - t0
+
+        ns0, t_probe = run_oracle(min(n, max(d_eff, 1 << 16)))
+        ns = int(min(n, ns0 * args.cpu_seconds / max(t_probe, 1e-3)))
+        ns, t_cpu = run_oracle(ns) if ns > ns0 else (ns0, t_probe)
+        cpu = {"value": round(4.0 * K * ns / t_cpu / 1e9, 5), "unit": "GB/s", "cores": 1,
+               "kind": "oracle",
+               "sample": f"first {ns} elements of each of the {K} gradients: {K} x encode + 1 x "
+                         f"decode+step, {t_cpu:.1f} s single-threaded"}
+
+    out = {
+        "metric": "Encode and Decode+accumulate GB/s of fp32 gradient; % of MI355X HBM peak",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: n={n}, s={w.s}, d={w.d}, "
+                               f"code={['sparse Elias', 'dense Elias', 'fixed width'][w.code]}, K={K}",
+                   "n": n, "s": w.s, "d": w.d, "K": K, "eta": w.eta,
+                   "bits_per_element": round(8 * msg_bytes_avg / n, 4),
+                   "message_bytes": int(msg_bytes_avg)},
+        "encode_GBps": round(enc_gbps, 1), "encode_frac_hbm_peak": round(enc_gbps / HBM_PEAK_GBPS, 4),
+        "decode_step_GBps": round(dec_gbps, 1),
+        "encode_ms_per_message": round(enc_ms, 4), "decode_step_ms": round(dec_ms, 4),
+        "copy_ceiling_GBps": round(copy_gbps, 1),
+        "roofline": roofline, "roofline_other": roofline_other,
+        "kernels": {k_: {"ms_avg": round(v["ms_avg"], 4), "launches": v["launches"]}
+                    for k_, v in kern.items()},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
