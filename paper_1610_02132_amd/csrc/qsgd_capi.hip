@@ -10,6 +10,7 @@
 
 #include "qsgd.h"
 #include "qsgd_device.hpp"
+#include "qsgd_encode_wave.hpp"
 #include "qsgd_kernels.hpp"
 
 namespace {
@@ -119,7 +120,9 @@ void plan_encode(const Geometry& g, uint32_t teams_target, EncodePlan& pl) {
     pl.sub_words = (uint32_t)(((sub_bits + 31) / 32 + 2 + 1) & ~(uint64_t)1);
     pl.ws_bytes = kTotalsBytes + (uint64_t)pl.teams * pl.region_words * 4;
   }
-  pl.lds = 4 * ((size_t)pl.dst_words + (size_t)pl.tw * pl.sub_words) + 8 * pl.tw + 16 * pl.tw + 16;
+  const size_t ring_words = g.code == QSGD_CODE_SPARSE ? kRingWords : 0;
+  pl.lds = 4 * ((size_t)pl.dst_words + (size_t)pl.tw * (pl.sub_words + ring_words)) + 8 * pl.tw +
+           16 * pl.tw + 16;
 }
 
 // ---- optional kernel timing -----------------------------------------------------

@@ -13,23 +13,12 @@
 // for another one.  Fixed-width strings have closed-form offsets and go straight
 // to the message.
 #include "qsgd_device.hpp"
+#include "qsgd_encode_wave.hpp"
 #include "qsgd_kernels.hpp"
 
 namespace qsgd {
 
 namespace {
-
-// Per-wave summary of the records it produced for the current bucket.
-struct WaveInfo {
-  uint32_t first_pos;  // 1-based position of its first nonzero (0: none)
-  uint32_t last_pos;   // 1-based position of its last nonzero
-  uint32_t bits;       // bits in its sub-stream (first record's gap left out)
-};
-
-template <int TW>
-__device__ __forceinline__ void team_sync() {
-  __syncthreads();  // one wavefront per team: only orders the LDS traffic
-}
 
 // Loads the float4 of this lane for the chunk starting `eoff` elements into the
 // bucket; elements at or past m read as 0.
@@ -52,15 +41,18 @@ __device__ __forceinline__ float4 load_quad(const float* __restrict__ gb, uint32
 template <int TW, int CPW, int CODE>
 __global__ __launch_bounds__(64 * TW) void k_encode_bucket(EncodeArgs a) {
   extern __shared__ uint32_t smem[];
-  // LDS: [dst image of the bucket string][TW sub-streams][reduction scratch]
+  // LDS: [dst image of the bucket string][TW sub-streams][TW record rings][scratch]
+  constexpr uint32_t kRingW = (CODE == QSGD_CODE_SPARSE) ? kRingWords : 0u;
   uint32_t* const dst = smem;
   uint32_t* const sub_all = smem + a.dst_words;
-  double* const red = reinterpret_cast<double*>(smem + a.dst_words + TW * a.sub_words);
-  WaveInfo* const winfo = reinterpret_cast<WaveInfo*>(red + TW);
+  uint32_t* const ring_all = sub_all + TW * a.sub_words;
+  double* const red = reinterpret_cast<double*>(ring_all + TW * kRingW);
+  WaveOut* const winfo = reinterpret_cast<WaveOut*>(red + TW);
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   uint32_t* const sub = sub_all + wave * a.sub_words;
+  uint32_t* const ring = ring_all + wave * kRingW;
 
   for (uint32_t j = tid; j < a.dst_words + TW * a.sub_words; j += 64 * TW) smem[j] = 0;
 
@@ -210,102 +202,24 @@ __global__ __launch_bounds__(64 * TW) void k_encode_bucket(EncodeArgs a) {
     }
 
     // ---- Elias codes: each wave builds its sub-stream in LDS -----------------
-    uint32_t wbits = 0;      // bits in this wave's sub-stream so far
-    uint32_t first_pos = 0;  // 1-based position of the wave's first nonzero
-    uint32_t carry = 0;      // 1-based position of the latest nonzero so far
-#pragma unroll
-    for (int c = 0; c < CPW; ++c) {
-      const uint32_t cstart = (uint32_t)(wave * CPW + c) * kChunk;
-      if (cstart >= m) continue;
-      const uint32_t e0 = cstart + lane * 4;
-      const uint64_t q = (base + e0) >> 2;
-      uint32_t r[4];
-      philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.stream_id, a.iteration, a.key0,
-                    a.key1, r);
-      uint32_t z[4];
-      z[0] = quantize_one(v[c].x, inv, s_f, s, r[0]);
-      z[1] = quantize_one(v[c].y, inv, s_f, s, r[1]);
-      z[2] = quantize_one(v[c].z, inv, s_f, s, r[2]);
-      z[3] = quantize_one(v[c].w, inv, s_f, s, r[3]);
-      const uint32_t neg[4] = {v[c].x < 0.f ? 1u : 0u, v[c].y < 0.f ? 1u : 0u,
-                               v[c].z < 0.f ? 1u : 0u, v[c].w < 0.f ? 1u : 0u};
-      uint64_t code[4];
-      uint32_t len[4] = {0, 0, 0, 0};
-
-      if (CODE == QSGD_CODE_DENSE) {
-        // Code'_s: sign bit, Elias(level + 1), for every coordinate below m.
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (e0 + j < m) {
-            uint64_t lc; uint32_t ll;
-            omega_encode(z[j] + 1u, lc, ll);
-            code[j] = ((uint64_t)neg[j] << ll) | lc;
-            len[j] = ll + 1u;
-          }
-        }
-      } else {
-        // Code_s: Elias(gap), sign bit, Elias(level) per nonzero.  The gap of the
-        // wave's very first nonzero is left out here and added when the team's
-        // sub-streams are joined (it depends on the waves before this one).
-        const uint32_t nzm = (z[0] ? 1u : 0u) | (z[1] ? 2u : 0u) | (z[2] ? 4u : 0u) |
-                             (z[3] ? 8u : 0u);
-        const uint64_t anyb = __ballot(nzm != 0);
-        if (anyb == 0) continue;  // whole chunk quantized to zero
-        const uint32_t hi = nzm ? 31u - (uint32_t)__clz(nzm) : 0u;
-        const uint64_t hb0 = __ballot(nzm && (hi & 1u));
-        const uint64_t hb1 = __ballot(nzm && (hi & 2u));
-        const uint64_t below = anyb & ((1ull << lane) - 1ull);
-        uint32_t prev = carry;
-        if (below) {
-          const int P = 63 - __clzll((long long)below);
-          prev = cstart + 4u * P + (uint32_t)((hb0 >> P) & 1ull) +
-                 2u * (uint32_t)((hb1 >> P) & 1ull) + 1u;
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (z[j]) {
-            const uint32_t pos = e0 + j + 1u;
-            uint64_t lc; uint32_t ll;
-            omega_encode(z[j], lc, ll);
-            uint64_t cw = ((uint64_t)neg[j] << ll) | lc;
-            uint32_t cl = ll + 1u;
-            if (prev != 0) {
-              uint64_t gc; uint32_t gl;
-              omega_encode(pos - prev, gc, gl);
-              cw |= gc << cl;
-              cl += gl;
-            }
-            code[j] = cw;
-            len[j] = cl;
-            prev = pos;
-          }
-        }
-        const int F = __ffsll((unsigned long long)anyb) - 1;
-        const int L = 63 - __clzll((long long)anyb);
-        if (first_pos == 0)
-          first_pos = cstart + 4u * F + (uint32_t)(__ffs((int)lane_bcast(nzm, F)) - 1) + 1u;
-        carry = cstart + 4u * L + (31u - (uint32_t)__clz(lane_bcast(nzm, L))) + 1u;
-      }
-
-      const uint32_t tot = len[0] + len[1] + len[2] + len[3];
-      const uint32_t incl = wave_incl_scan_u32(tot, lane);
-      uint32_t off = wbits + incl - tot;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (len[j]) {
-          lds_emit(sub, off, code[j], len[j]);
-          off += len[j];
-        }
-      }
-      wbits += lane_bcast(incl, 63);
+    QuantCtx qc;
+    qc.inv = inv; qc.s_f = s_f; qc.s = s; qc.key0 = a.key0; qc.key1 = a.key1;
+    qc.stream_id = a.stream_id; qc.iteration = a.iteration;
+    WaveOut wo;
+    wo.first_pos = 0; wo.last_pos = 0; wo.bits = 0;
+    {
+      const uint32_t wstart = (uint32_t)wave * CPW * kChunk;  // bucket position of this wave
+      const uint32_t wlen = wstart < m ? min((uint32_t)CPW * kChunk, m - wstart) : 0u;
+      const int nchunks = (int)((wlen + kChunk - 1) / kChunk);
+      if (CODE == QSGD_CODE_SPARSE)
+        encode_sparse_wave<CPW, false>(v, nchunks, wstart, base + wstart, lane, qc, ring, sub, wo);
+      else
+        encode_dense_wave<CPW>(v, nchunks, wlen, base + wstart, lane, qc, sub, wo);
     }
+    const uint32_t wbits = wo.bits;
 
     // ---- join the sub-streams into the bucket string --------------------------
-    if (lane == 0) {
-      winfo[wave].first_pos = first_pos;
-      winfo[wave].last_pos = carry;
-      winfo[wave].bits = wbits;
-    }
+    if (lane == 0) winfo[wave] = wo;
     __syncthreads();
     uint32_t cursor = 32;  // after the scale
     uint32_t my_start = 0, my_glen = 0, my_gap = 0;
@@ -313,7 +227,7 @@ __global__ __launch_bounds__(64 * TW) void k_encode_bucket(EncodeArgs a) {
       uint32_t prev_last = 0;
 #pragma unroll
       for (int w = 0; w < TW; ++w) {
-        const WaveInfo wi = winfo[w];
+        const WaveOut wi = winfo[w];
         uint32_t glen = 0, gap = 0;
         if (CODE == QSGD_CODE_SPARSE && wi.first_pos) {
           gap = wi.first_pos - prev_last;

@@ -1,0 +1,195 @@
+// Wavefront-level encoders: one wavefront turns up to CPW chunks of 256 values
+// (held in registers, 4 per lane) into a bit "sub-stream" in LDS.
+//
+// Code_s (Sec. 3.1, App. A.2) only has records for nonzero levels, and in its
+// intended regime almost every level is zero.  So the work is split in two:
+//   stage 1, every element: one Philox block per float4, t = |v| * fl(s/scale),
+//            and the test "level != 0", which is exactly u < t (for t >= 1 it
+//            holds since u < 1; for t < 1 the round-up probability is t itself).
+//            Survivors are compacted, in position order, into a small LDS ring.
+//   stage 2, survivors only, one per lane: level from Eq. (2), Elias(gap), sign,
+//            Elias(level), a wavefront prefix sum of the code lengths and the OR
+//            of the code words into the sub-stream.
+// The gap of a wavefront's first record depends on the wavefronts before it and
+// is left out; whoever joins the sub-streams adds it.
+#pragma once
+
+#include "qsgd_device.hpp"
+
+namespace qsgd {
+
+constexpr uint32_t kRing = 256;  // records in a wavefront's ring (power of two)
+constexpr uint32_t kRingWords = 3 * kRing;
+
+struct QuantCtx {
+  float inv;   // fl(s / scale), 0 for an all-zero bucket
+  float s_f;
+  uint32_t s;
+  uint32_t key0, key1, stream_id, iteration;
+};
+
+struct WaveOut {
+  uint32_t first_pos;  // 1-based bucket position of the first record (0: none)
+  uint32_t last_pos;   // 1-based bucket position of the last record
+  uint32_t bits;       // bits in the sub-stream
+};
+
+// Number of set bits of `mask` below this lane.
+__device__ __forceinline__ uint32_t bits_below(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                   __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// Stage 2 on `take` (1..64) records starting at ring slot `head`.
+// WIDE: gaps may need more than 21 bits, emit gap and (sign, level) separately.
+template <bool WIDE>
+__device__ __forceinline__ void sparse_flush(const uint32_t* ring, uint32_t head, uint32_t take,
+                                             int lane, const QuantCtx& q, uint32_t* sub,
+                                             WaveOut& out) {
+  const uint32_t idx = (head + (uint32_t)lane) & (kRing - 1);
+  const bool live = (uint32_t)lane < take;
+  uint32_t pos = 0, len = 0, gl = 0, cl = 0;
+  uint64_t gc = 0, cw = 0;
+  if (live) {
+    pos = ring[idx];
+    const float ts = __uint_as_float(ring[kRing + idx]);
+    const uint32_t word = ring[2 * kRing + idx];
+    const uint32_t prev = lane == 0 ? out.last_pos : ring[(idx - 1u) & (kRing - 1)];
+    const float t = fabsf(ts);
+    const float fl = floorf(t);
+    const float p = t - fl;
+    const float u = (float)(word >> 8) * (1.0f / 16777216.0f);
+    const uint32_t z = (fl >= q.s_f) ? q.s : (uint32_t)fl + ((u < p) ? 1u : 0u);
+    uint64_t lc; uint32_t ll;
+    omega_encode(z, lc, ll);
+    cw = ((uint64_t)(ts < 0.f ? 1u : 0u) << ll) | lc;
+    cl = ll + 1u;
+    if (prev != 0) omega_encode(pos - prev, gc, gl);
+    len = gl + cl;
+  }
+  const uint32_t incl = wave_incl_scan_u32(len, lane);
+  const uint32_t off = out.bits + incl - len;
+  if (live) {
+    if (WIDE) {
+      if (gl) lds_emit(sub, off, gc, gl);
+      lds_emit(sub, off + gl, cw, cl);
+    } else {
+      lds_emit(sub, off, (gc << cl) | cw, len);
+    }
+  }
+  out.bits += lane_bcast(incl, 63);
+  if (out.first_pos == 0) out.first_pos = lane_bcast(pos, 0);
+  out.last_pos = lane_bcast(pos, (int)take - 1);
+}
+
+// Code_s sub-stream of the wavefront's values.
+//   v[c]      lane's float4 of chunk c (zeros past the end of the data)
+//   nchunks   chunks that hold data (<= CPW)
+//   pos0      bucket position (0-based) of the wavefront's first value
+//   gidx0     global index of the wavefront's first value (multiple of 4)
+//   ring      kRingWords words of LDS private to this wavefront
+//   sub       zero-initialised LDS words private to this wavefront
+template <int CPW, bool WIDE>
+__device__ __forceinline__ void encode_sparse_wave(const float4 (&v)[CPW], int nchunks,
+                                                   uint32_t pos0, uint64_t gidx0, int lane,
+                                                   const QuantCtx& q, uint32_t* ring,
+                                                   uint32_t* sub, WaveOut& out) {
+  uint32_t head = 0, count = 0;
+#pragma unroll
+  for (int c = 0; c < CPW; ++c) {
+    if (c >= nchunks) break;
+    const uint64_t quad = (gidx0 >> 2) + (uint64_t)c * 64u + (uint64_t)lane;
+    uint32_t r[4];
+    philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), q.stream_id, q.iteration, q.key0,
+                  q.key1, r);
+    const float ts[4] = {v[c].x * q.inv, v[c].y * q.inv, v[c].z * q.inv, v[c].w * q.inv};
+    bool nz[4];
+    uint64_t mk[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float u = (float)(r[j] >> 8) * (1.0f / 16777216.0f);
+      nz[j] = u < fabsf(ts[j]);
+      mk[j] = __ballot(nz[j]);
+    }
+    const uint32_t cnt = (uint32_t)(__popcll(mk[0]) + __popcll(mk[1]) + __popcll(mk[2]) +
+                                    __popcll(mk[3]));
+    if (cnt == 0) continue;
+    while (count + cnt > kRing) {  // make room (only in very dense data)
+      const uint32_t take = min(64u, count);
+      sparse_flush<WIDE>(ring, head, take, lane, q, sub, out);
+      head += take;
+      count -= take;
+    }
+    uint32_t slot = head + count + bits_below(mk[0]) + bits_below(mk[1]) + bits_below(mk[2]) +
+                    bits_below(mk[3]);
+    const uint32_t p1 = pos0 + (uint32_t)c * kChunk + (uint32_t)lane * 4u + 1u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (nz[j]) {
+        const uint32_t i = slot & (kRing - 1);
+        ring[i] = p1 + j;
+        ring[kRing + i] = __float_as_uint(ts[j]);
+        ring[2 * kRing + i] = r[j];
+        ++slot;
+      }
+    }
+    count += cnt;
+    __builtin_amdgcn_wave_barrier();
+    while (count >= 64u) {
+      sparse_flush<WIDE>(ring, head, 64u, lane, q, sub, out);
+      head += 64u;
+      count -= 64u;
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  while (count > 0) {
+    const uint32_t take = min(64u, count);
+    sparse_flush<WIDE>(ring, head, take, lane, q, sub, out);
+    head += take;
+    count -= take;
+  }
+}
+
+// Code'_s sub-stream (App. A.3): every coordinate sends its sign and Elias(level+1).
+//   len_valid  values that exist in the wavefront's range (the rest is padding)
+template <int CPW>
+__device__ __forceinline__ void encode_dense_wave(const float4 (&v)[CPW], int nchunks,
+                                                  uint32_t len_valid, uint64_t gidx0, int lane,
+                                                  const QuantCtx& q, uint32_t* sub,
+                                                  WaveOut& out) {
+#pragma unroll
+  for (int c = 0; c < CPW; ++c) {
+    if (c >= nchunks) break;
+    const uint64_t quad = (gidx0 >> 2) + (uint64_t)c * 64u + (uint64_t)lane;
+    uint32_t r[4];
+    philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), q.stream_id, q.iteration, q.key0,
+                  q.key1, r);
+    const float vv[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+    const uint32_t e0 = (uint32_t)c * kChunk + (uint32_t)lane * 4u;
+    uint64_t code[4];
+    uint32_t len[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (e0 + j < len_valid) {
+        const uint32_t z = quantize_one(vv[j], q.inv, q.s_f, q.s, r[j]);
+        uint64_t lc; uint32_t ll;
+        omega_encode(z + 1u, lc, ll);
+        code[j] = ((uint64_t)(vv[j] < 0.f ? 1u : 0u) << ll) | lc;
+        len[j] = ll + 1u;
+      }
+    }
+    const uint32_t tot = len[0] + len[1] + len[2] + len[3];
+    const uint32_t incl = wave_incl_scan_u32(tot, lane);
+    uint32_t off = out.bits + incl - tot;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (len[j]) {
+        lds_emit(sub, off, code[j], len[j]);
+        off += len[j];
+      }
+    }
+    out.bits += lane_bcast(incl, 63);
+  }
+}
+
+}  // namespace qsgd
