@@ -86,7 +86,7 @@ def main() -> int:
             q.qsgd_encode(params(k), grads[k], msgs[k], ws)
         q.qsgd_sgd_step(params(0), msgs, w.eta, x, ws)
 
-    for _ in range(args.warmup):
+    for _ in range(max(args.warmup, 1)):   # at least one untimed pass fills the messages
         one_step()
     torch.cuda.synchronize()
     sizes = []

@@ -22,47 +22,67 @@ __device__ __forceinline__ void flag_corrupt(uint32_t* status) {
   atomicExch(status, (uint32_t)QSGD_ERR_CORRUPT);
 }
 
-// MSB-first bit reader over words [0, nwords) of one string; past the end it
-// supplies zeros and never touches memory.
-struct BitReader {
-  const uint32_t* w;
-  uint32_t nwords, widx;
-  uint64_t buf;       // next bits, most significant first
-  uint32_t avail;     // valid bits in buf (kept above 32)
-  uint32_t consumed;  // stream position of the next bit
+// Recursive Elias code (App. A.2), decoder rule unrolled: N = 1; a 0 bit outputs N,
+// a 1 bit opens an (N+1)-bit group whose value is the new N.  `w` holds the next
+// 32 stream bits, first bit on top.  G = most groups accepted (G = 1: k <= 3,
+// 2: k <= 15, 3: k < 2^16, 4: every code word of at most 32 bits, k < 2^20).
+// Returns 0 (len 0) for anything longer or malformed.
+template <int G>
+__device__ __forceinline__ uint32_t omega_peek(uint32_t w, uint32_t& len) {
+  const uint32_t t0 = w >> 31;
+  const uint32_t g1 = w >> 30;            // first group, 2 bits: 2 or 3
+  const uint32_t w1 = w << 2;
+  const uint32_t t1 = w1 >> 31;
+  uint32_t v = 0, l = 0;
+  if constexpr (G >= 2) {
+    const uint32_t n1 = g1 + 1u;            // 3 or 4
+    const uint32_t g2 = w1 >> (32u - n1);   // 4..15
+    const uint32_t w2 = w1 << n1;
+    const uint32_t t2 = w2 >> 31;
+    if constexpr (G >= 3) {
+      const uint32_t n2 = g2 + 1u;            // 5..16
+      const uint32_t g3 = w2 >> (32u - n2);   // 16..65535
+      const uint32_t w3 = w2 << n2;
+      const uint32_t t3 = w3 >> 31;
+      const uint32_t l3 = 3u + n1 + n2;       // length when the third group is the value
+      if constexpr (G >= 4) {
+        const uint32_t n3 = min(g3 + 1u, 31u);  // only used when the whole word fits 32 bits
+        const uint32_t g4 = w3 >> (32u - n3);
+        // a fourth group only counts if it and its closing 0 lie inside the 32 bits
+        const bool fits4 = l3 + g3 + 1u <= 32u && ((w3 << n3) >> 31) == 0u;
+        if (t3 && fits4) { v = g4; l = l3 + n3; }
+      }
+      if (!t3) { v = g3; l = l3; }
+    }
+    if (!t2) { v = g2; l = 3u + n1; }
+  }
+  if (!t1) { v = g1; l = 3u; }
+  if (!t0) { v = 1u; l = 1u; }
+  len = l;
+  return v;
+}
 
-  __device__ __forceinline__ void refill() {
-    while (avail <= 32u) {
-      const uint32_t nw = (widx < nwords) ? w[widx] : 0u;
-      ++widx;
-      buf |= (uint64_t)nw << (32u - avail);
-      avail += 32u;
-    }
+typedef const __attribute__((address_space(3))) uint32_t* lds_words;
+template <bool STAGED> struct WordPtr;
+template <> struct WordPtr<true> { typedef lds_words type; };         // string copied to LDS
+template <> struct WordPtr<false> { typedef const uint32_t* type; };  // string in global memory
+
+// The 32 stream bits that start at bit `bitpos` of a string (bit j = bit 31-j%32 of
+// word j/32).  Words past the end read as zeros.
+template <bool STAGED>
+__device__ __forceinline__ uint32_t peek_bits(typename WordPtr<STAGED>::type w, uint32_t nwords,
+                                              uint32_t bitpos) {
+  const uint32_t wi = bitpos >> 5, off = bitpos & 31u;
+  uint32_t hi, lo;
+  if constexpr (STAGED) {  // the LDS copy has slack behind it: no bounds needed
+    hi = w[wi];
+    lo = w[wi + 1];
+  } else {
+    hi = wi < nwords ? w[wi] : 0u;
+    lo = wi + 1 < nwords ? w[wi + 1] : 0u;
   }
-  __device__ __forceinline__ void init(const uint32_t* words, uint32_t n, uint32_t first_word) {
-    w = words; nwords = n; widx = first_word; buf = 0; avail = 0;
-    consumed = first_word * 32u;
-    refill();
-  }
-  __device__ __forceinline__ uint32_t take(uint32_t nbits) {  // 1..32
-    const uint32_t v = (uint32_t)(buf >> (64u - nbits));
-    buf <<= nbits;
-    avail -= nbits;
-    consumed += nbits;
-    refill();
-    return v;
-  }
-  // Decoder rule of the recursive Elias code (App. A.2): N = 1; a 0 bit outputs N;
-  // a 1 bit opens an (N+1)-bit group whose value is the new N.  0 = malformed.
-  __device__ __forceinline__ uint32_t omega() {
-    uint32_t N = 1;
-    for (;;) {
-      if ((buf >> 63) == 0) { take(1); return N; }
-      if (N > 31u) return 0;
-      N = take(N + 1u);
-    }
-  }
-};
+  return (uint32_t)((((uint64_t)hi << 32) | lo) >> (32u - off));
+}
 
 }  // namespace
 
@@ -168,73 +188,99 @@ __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
 }
 
 // ---- Elias codes: one lane per string, gw buckets x K messages per wavefront -------
-__global__ __launch_bounds__(64) void k_decode_elias(DecodeArgs a) {
-  if (*a.status != 0) return;
-  extern __shared__ uint32_t smem[];
-  // LDS: [acc: gw*win floats][queues: 64*rec words][counts: 64][scales: 64]
-  float* const acc = reinterpret_cast<float*>(smem);
-  uint32_t* const queue = smem + a.gw * a.win;
-  uint32_t* const counts = queue + 64u * a.rec;
-  float* const scales = reinterpret_cast<float*>(counts + 64);
+// Per wavefront: (1) the strings of its gw buckets are contiguous in each message,
+// so they are copied to LDS with coalesced loads (when they fit; else lanes read
+// them from global memory); (2) per window of `win` bucket positions the x values
+// are fetched into registers first, so that their latency hides behind the
+// parsing; (3) every lane parses ahead into its own small ring of records, and
+// records are applied to the LDS accumulator in message order, but only up to
+// the position every string has been parsed to; (4) registers and accumulator
+// are combined and stored.
+constexpr int kMaxQuads = 16;   // float4 per lane per window: gw * winp <= 4096 floats
+constexpr uint32_t kStrSlack = 4;  // readable words behind the staged strings
 
+// CODE: sparse or dense Elias code.  LG: groups a level's code word may have.
+template <int CODE, int LG, bool STAGED>
+__device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* acc, uint32_t* queue,
+                                                  uint32_t* counts, uint32_t* heads,
+                                                  float* scales, const uint32_t* starts,
+                                                  uint32_t* strs, uint32_t total, uint32_t b0,
+                                                  uint32_t gcount) {
+  constexpr bool kSparse = CODE == QSGD_CODE_SPARSE;
+  // a whole record in one 32-bit peek: gap <= 21 bits, sign, level <= 7 bits
+  constexpr bool kNarrow = !kSparse || LG <= 2;
+  const uint32_t K = a.K, gw = a.gw, win = a.win, winp = a.winp, rec = a.rec, s = a.s;
   const int lane = threadIdx.x;
-  const uint32_t K = a.K, gw = a.gw, win = a.win, rec = a.rec, s = a.s;
-  const bool sparse = a.code == QSGD_CODE_SPARSE;
-  const uint32_t b0 = blockIdx.x * gw;
+  const uint64_t pay = (uint64_t)H_WORDS + a.table_words;
 
   // ---- open this lane's string -----------------------------------------------------
   const uint32_t g = lane / K, k = lane - g * K;
   const uint32_t b = b0 + g;
   bool have = false;      // a decoded record is waiting in (pend_pos, pend_lev, pend_neg)
   uint32_t m = 0;         // elements in this lane's bucket
-  uint32_t endbit = 0;    // sparse: records end here
+  uint32_t endbit = 0;    // records end here
+  uint32_t bitpos = 32;   // next unread bit (after the scale)
+  uint32_t nwords = 0;
   uint32_t pend_pos = 0, pend_lev = 0, pend_neg = 0;  // pend_pos is 1-based
-  BitReader rd;
-  rd.init(nullptr, 0, 0);
+  typename WordPtr<STAGED>::type str = nullptr;
   bool open = false;
-  if (g < gw && b < a.nb) {
+  float my_scale = 0.f;
+  if (g < gcount) {
     m = (uint32_t)min((uint64_t)a.d, a.n - (uint64_t)b * a.d);
     const uint32_t* msg = a.msgs[k];
     const uint32_t o0 = msg[H_WORDS + b], o1 = msg[H_WORDS + b + 1];
-    const uint64_t pay = (uint64_t)H_WORDS + a.table_words;
-    if (o0 < o1 && pay + o1 <= a.msg_words[k]) {
-      const uint32_t* str = msg + pay + o0;
-      const uint32_t nwords = o1 - o0;
-      scales[lane] = __uint_as_float(str[0]) / (float)s;
+    const uint32_t kr0 = msg[H_WORDS + b0];  // start of message k's range
+    if (o0 < o1 && kr0 <= o0 && pay + o1 <= a.msg_words[k] && (!STAGED || o1 - kr0 <= total)) {
+      nwords = o1 - o0;
+      if constexpr (STAGED) str = (lds_words)(strs + starts[k] + (o0 - kr0));
+      else str = msg + pay + o0;
+      my_scale = __uint_as_float(str[0]) / (float)s;
       open = true;
-      if (sparse) {
+      if (kSparse) {
         const uint32_t last = str[nwords - 1];
         endbit = nwords * 32u - 1u - (uint32_t)(__ffs((int)last) - 1);
         if (last == 0 || endbit < 32u) open = false;
       } else {
         endbit = nwords * 32u;
       }
-      if (open) rd.init(str, nwords, 1);
     }
     if (!open) flag_corrupt(a.status);
   }
-  if (!open) scales[lane] = 0.f;
+  scales[lane] = open ? my_scale : 0.f;
 
   // Reads the next record into pend_*; clears `have` at the end of the string.
   auto advance = [&]() {
-    if (sparse) {
-      if (rd.consumed >= endbit) { have = false; return; }
-      const uint32_t gap = rd.omega();
-      pend_neg = rd.take(1);
-      const uint32_t lev = rd.omega();
+    if (kSparse) {
+      if (bitpos >= endbit) { have = false; return; }
+      uint32_t gl, ll, gap, lev;
+      const uint32_t w = peek_bits<STAGED>(str, nwords, bitpos);
+      gap = omega_peek<3>(w, gl);
+      if (kNarrow) {
+        const uint32_t x = w << gl;
+        pend_neg = x >> 31;
+        lev = omega_peek<LG>(x << 1, ll);
+      } else {
+        const uint32_t x = peek_bits<STAGED>(str, nwords, bitpos + gl);
+        pend_neg = x >> 31;
+        lev = omega_peek<LG>(x << 1, ll);
+      }
+      bitpos += gl + 1u + ll;
       pend_pos += gap;
       pend_lev = lev;
-      if (gap == 0 || lev == 0 || lev > s || pend_pos > m || rd.consumed > endbit) {
+      if (gap == 0 || lev == 0 || lev > s || pend_pos > m || bitpos > endbit) {
         flag_corrupt(a.status);
         have = false;
       }
     } else {
       if (pend_pos >= m) { have = false; return; }
-      pend_neg = rd.take(1);
-      const uint32_t lev1 = rd.omega();
+      uint32_t ll;
+      const uint32_t w = peek_bits<STAGED>(str, nwords, bitpos);
+      const uint32_t lev1 = omega_peek<LG>(w << 1, ll);
+      bitpos += 1u + ll;
+      pend_neg = w >> 31;
       pend_pos += 1;
       pend_lev = lev1 - 1u;
-      if (lev1 == 0 || lev1 > s + 1u || rd.consumed > endbit) {
+      if (lev1 == 0 || lev1 > s + 1u || bitpos > endbit) {
         flag_corrupt(a.status);
         have = false;
       }
@@ -242,88 +288,181 @@ __global__ __launch_bounds__(64) void k_decode_elias(DecodeArgs a) {
   };
   if (open) { have = true; advance(); }
 
-  for (uint32_t j = lane; j < gw * win; j += 64) acc[j] = 0.f;
+  for (uint32_t j = lane; j < gw * winp; j += 64) acc[j] = 0.f;
   __syncthreads();
 
+  const uint32_t nq = gw * winp / kChunk;  // float4 per lane per window (<= kMaxQuads)
+  uint32_t qhead = 0, qcnt = 0;            // this lane's ring of queued records
+  const uint32_t g2 = lane / rec, r = lane - g2 * rec;  // apply role: bucket g2, ring slot r
   for (uint32_t ws = 0; ws < a.d; ws += win) {
-    const uint32_t wend = ws + win;  // records with pend_pos <= wend fall in this window
-    // ---- rounds: fill the queues, then apply them message by message --------------
-    // A round may only apply positions that EVERY string has already queued up
-    // to, or an element could receive message 5's term before message 2's.  The
-    // limit is the smallest position some full queue still has pending, minus 1;
-    // queued records past it stay in the queue for the next round.
-    uint32_t cnt = 0;
+    const uint32_t wend = ws + win;  // positions (1-based) up to wend fall in this window
+    // ---- fetch this window of x into registers (latency hides behind the parsing) ----
+    float4 xr[kMaxQuads];
+    uint32_t gg = 0, i0 = 0;  // bucket and offset of quad qi (wave-uniform)
+#pragma unroll
+    for (int qi = 0; qi < kMaxQuads; ++qi) {
+      xr[qi] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if ((uint32_t)qi < nq) {
+        const uint32_t i = i0 + (uint32_t)lane * 4u;
+        if (gg < gcount) {
+          const uint64_t base = (uint64_t)(b0 + gg) * a.d;
+          const uint32_t mb = (uint32_t)min((uint64_t)a.d, a.n - base);
+          const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
+          const float* xp = a.x + base + ws + i;
+          if (i + 3 < cntw) {
+            xr[qi] = *reinterpret_cast<const float4*>(xp);
+          } else {
+            if (i + 0 < cntw) xr[qi].x = xp[0];
+            if (i + 1 < cntw) xr[qi].y = xp[1];
+            if (i + 2 < cntw) xr[qi].z = xp[2];
+          }
+        }
+        i0 += kChunk;
+        if (i0 >= winp) { i0 = 0; ++gg; }
+      }
+    }
+    // ---- rounds: parse ahead into the rings, apply what is due --------------------------
+    // A position may only be applied once EVERY string has been parsed past it,
+    // or an element could receive message 5's term before message 2's.  `limit`
+    // is the smallest position still pending in any string, minus 1, capped at
+    // the window end; queued records past it wait in the ring.
     for (;;) {
-      while (have && pend_pos <= wend && cnt < rec) {
-        if (pend_lev)
-          queue[lane * rec + cnt++] = (pend_pos - 1u - ws) | (pend_neg << 12) | (pend_lev << 13);
+      while (have && qcnt < rec) {
+        if (pend_lev) {
+          queue[lane * rec + ((qhead + qcnt) & (rec - 1))] =
+              (pend_pos - 1u) | (pend_neg << 13) | (pend_lev << 14);
+          ++qcnt;
+        }
         advance();
       }
-      const bool more = have && pend_pos <= wend;  // stopped on a full queue
-      uint32_t limit = more ? pend_pos - 1u : wend;
+      uint32_t limit = have ? pend_pos - 1u : 0xFFFFFFFFu;
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) limit = min(limit, (uint32_t)__shfl_xor((int)limit, o, kWave));
-      const uint32_t rel_limit = limit - ws;  // window-relative positions below this are due
-      counts[lane] = cnt;
+      limit = min(limit, wend);   // 0-based positions below `limit` are due
+      counts[lane] = qcnt;
+      heads[lane] = qhead;
       __syncthreads();
-      const uint32_t g2 = lane / rec, r = lane - g2 * rec;
       for (uint32_t kk = 0; kk < K; ++kk) {
         if (g2 < gw) {
           const uint32_t sl = g2 * K + kk;
           if (r < counts[sl]) {
-            const uint32_t q = queue[sl * rec + r];
-            if ((q & 0xFFFu) < rel_limit) {
-              const float mag = scales[sl] * (float)(q >> 13);
-              acc[g2 * win + (q & 0xFFFu)] += ((q >> 12) & 1u) ? -mag : mag;
+            const uint32_t q = queue[sl * rec + ((heads[sl] + r) & (rec - 1))];
+            const uint32_t p0 = q & 0x1FFFu;
+            if (p0 < limit) {
+              const float mag = scales[sl] * (float)(q >> 14);
+              acc[g2 * winp + (p0 - ws)] += ((q >> 13) & 1u) ? -mag : mag;
             }
           }
         }
         __syncthreads();
       }
-      // keep what was not due yet at the front of the queue
-      if (limit == wend) {
-        cnt = 0;
-      } else {
-        uint32_t done = 0;
-        while (done < cnt && (queue[lane * rec + done] & 0xFFFu) < rel_limit) ++done;
-        for (uint32_t i = done; i < cnt; ++i) queue[lane * rec + i - done] = queue[lane * rec + i];
-        cnt -= done;
+      // drop what was applied from the front of the ring
+      while (qcnt && (queue[lane * rec + qhead] & 0x1FFFu) < limit) {
+        qhead = (qhead + 1u) & (rec - 1);
+        --qcnt;
       }
-      if (__ballot(more || cnt != 0) == 0) break;
+      if (limit == wend) break;   // uniform: every string is parsed past this window
     }
-    // ---- stream the window against x -------------------------------------------------
-    for (uint32_t gg = 0; gg < gw; ++gg) {
-      const uint32_t bb = b0 + gg;
-      if (bb >= a.nb) break;
-      const uint64_t base = (uint64_t)bb * a.d;
-      const uint32_t mb = (uint32_t)min((uint64_t)a.d, a.n - base);
-      if (ws >= mb) continue;
-      const uint32_t cntw = min(win, mb - ws);
-      float* xw = a.x + base + ws;
-      float* aw = acc + gg * win;
-      for (uint32_t i = lane * 4; i < cntw; i += kChunk) {
-        if (i + 3 < cntw) {
-          const float4 av = *reinterpret_cast<float4*>(aw + i);
-          *reinterpret_cast<float4*>(aw + i) = make_float4(0.f, 0.f, 0.f, 0.f);
-          float4 xv = *reinterpret_cast<float4*>(xw + i);
-          if (a.step) {
-            xv.x = fmaf(-a.c, av.x, xv.x); xv.y = fmaf(-a.c, av.y, xv.y);
-            xv.z = fmaf(-a.c, av.z, xv.z); xv.w = fmaf(-a.c, av.w, xv.w);
-          } else {
-            xv.x += av.x; xv.y += av.y; xv.z += av.z; xv.w += av.w;
-          }
-          *reinterpret_cast<float4*>(xw + i) = xv;
-        } else {
-          for (uint32_t j = i; j < cntw; ++j) {
-            const float av = aw[j];
-            aw[j] = 0.f;
-            xw[j] = a.step ? fmaf(-a.c, av, xw[j]) : xw[j] + av;
+    // ---- combine the accumulator with x and store ------------------------------------
+    gg = 0; i0 = 0;
+#pragma unroll
+    for (int qi = 0; qi < kMaxQuads; ++qi) {
+      if ((uint32_t)qi < nq) {
+        const uint32_t i = i0 + (uint32_t)lane * 4u;
+        if (gg < gcount) {
+          const uint64_t base = (uint64_t)(b0 + gg) * a.d;
+          const uint32_t mb = (uint32_t)min((uint64_t)a.d, a.n - base);
+          const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
+          float* xp = a.x + base + ws + i;
+          float* ap = acc + gg * winp + i;
+          if (i < cntw) {
+            const float4 av = *reinterpret_cast<float4*>(ap);
+            *reinterpret_cast<float4*>(ap) = make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 xv = xr[qi];
+            if (a.step) {
+              xv.x = fmaf(-a.c, av.x, xv.x); xv.y = fmaf(-a.c, av.y, xv.y);
+              xv.z = fmaf(-a.c, av.z, xv.z); xv.w = fmaf(-a.c, av.w, xv.w);
+            } else {
+              xv.x += av.x; xv.y += av.y; xv.z += av.z; xv.w += av.w;
+            }
+            if (i + 3 < cntw) {
+              *reinterpret_cast<float4*>(xp) = xv;
+            } else {
+              xp[0] = xv.x;
+              if (i + 1 < cntw) xp[1] = xv.y;
+              if (i + 2 < cntw) xp[2] = xv.z;
+            }
           }
         }
+        i0 += kChunk;
+        if (i0 >= winp) { i0 = 0; ++gg; }
       }
     }
     __syncthreads();
   }
+}
+
+template <int CODE, int LG>
+__global__ __launch_bounds__(64) void k_decode_elias(DecodeArgs a) {
+  if (*a.status != 0) return;
+  extern __shared__ uint32_t smem[];
+  // LDS: [acc: gw*winp floats][rings: 64*rec][counts 64][heads 64][scales 64][starts 64][strings]
+  const uint32_t K = a.K, gw = a.gw, winp = a.winp, rec = a.rec;
+  float* const acc = reinterpret_cast<float*>(smem);
+  uint32_t* const queue = smem + gw * winp;
+  uint32_t* const counts = queue + 64u * rec;
+  uint32_t* const heads = counts + 64;
+  float* const scales = reinterpret_cast<float*>(counts + 128);
+  uint32_t* const starts = counts + 192;
+  uint32_t* const strs = counts + 256;
+
+  const int lane = threadIdx.x;
+  const uint32_t b0 = blockIdx.x * gw;
+  const uint32_t gcount = min(gw, a.nb - b0);  // buckets this wavefront really has
+  const uint64_t pay = (uint64_t)H_WORDS + a.table_words;
+
+  // ---- stage the strings: message k's part is words [r0, r1) of its payload --------
+  uint32_t r0 = 0, rlen = 0;
+  bool range_ok = true;
+  if ((uint32_t)lane < K) {
+    const uint32_t* msg = a.msgs[lane];
+    r0 = msg[H_WORDS + b0];
+    const uint32_t r1 = msg[H_WORDS + b0 + gcount];
+    range_ok = r0 <= r1 && pay + r1 <= a.msg_words[lane];
+    rlen = range_ok ? r1 - r0 : 0u;
+  }
+  const uint32_t incl = wave_incl_scan_u32(rlen, lane);
+  const uint32_t total = lane_bcast(incl, 63);
+  const bool staged = total <= a.str_words;
+  if ((uint32_t)lane < K) starts[lane] = incl - rlen;
+  if (!range_ok) flag_corrupt(a.status);
+  if (staged) {
+    for (uint32_t kk = 0; kk < K; ++kk) {
+      const uint32_t len = lane_bcast(rlen, (int)kk);
+      const uint32_t l0 = lane_bcast(incl - rlen, (int)kk);
+      const uint32_t* src = a.msgs[kk] + pay + lane_bcast(r0, (int)kk);
+      for (uint32_t w = lane; w < len; w += 256) {
+        const uint32_t w1 = w + 64, w2 = w + 128, w3 = w + 192;
+        const uint32_t x0 = src[w];
+        const uint32_t x1 = w1 < len ? src[w1] : 0u;
+        const uint32_t x2 = w2 < len ? src[w2] : 0u;
+        const uint32_t x3 = w3 < len ? src[w3] : 0u;
+        strs[l0 + w] = x0;
+        if (w1 < len) strs[l0 + w1] = x1;
+        if (w2 < len) strs[l0 + w2] = x2;
+        if (w3 < len) strs[l0 + w3] = x3;
+      }
+    }
+    if ((uint32_t)lane < kStrSlack) strs[total + lane] = 0;
+  }
+  __syncthreads();
+
+  if (staged)
+    decode_elias_body<CODE, LG, true>(a, acc, queue, counts, heads, scales, starts, strs, total,
+                                      b0, gcount);
+  else
+    decode_elias_body<CODE, LG, false>(a, acc, queue, counts, heads, scales, starts, strs, total,
+                                       b0, gcount);
 }
 
 hipError_t launch_decode_check(const DecodeArgs& a, hipStream_t st) {
@@ -336,9 +475,25 @@ hipError_t launch_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t
   return hipGetLastError();
 }
 
-hipError_t launch_decode_elias(const DecodeArgs& a, uint32_t blocks, size_t lds, hipStream_t st) {
-  hipLaunchKernelGGL(k_decode_elias, dim3(blocks), dim3(64), lds, st, a);
+template <int CODE>
+static hipError_t launch_elias_code(const DecodeArgs& a, int lg, uint32_t blocks, size_t lds,
+                                    hipStream_t st) {
+  const dim3 grid(blocks), block(64);
+  switch (lg) {
+    case 1: hipLaunchKernelGGL((k_decode_elias<CODE, 1>), grid, block, lds, st, a); break;
+    case 2: hipLaunchKernelGGL((k_decode_elias<CODE, 2>), grid, block, lds, st, a); break;
+    case 3: hipLaunchKernelGGL((k_decode_elias<CODE, 3>), grid, block, lds, st, a); break;
+    default: hipLaunchKernelGGL((k_decode_elias<CODE, 4>), grid, block, lds, st, a); break;
+  }
   return hipGetLastError();
+}
+
+// Groups in the longest level code word: Elias(s) (sparse) or Elias(s + 1) (dense).
+hipError_t launch_decode_elias(const DecodeArgs& a, uint32_t blocks, size_t lds, hipStream_t st) {
+  const uint32_t top = a.code == QSGD_CODE_SPARSE ? a.s : a.s + 1u;
+  const int lg = top <= 3 ? 1 : top <= 15 ? 2 : top <= 65535 ? 3 : 4;
+  if (a.code == QSGD_CODE_SPARSE) return launch_elias_code<QSGD_CODE_SPARSE>(a, lg, blocks, lds, st);
+  return launch_elias_code<QSGD_CODE_DENSE>(a, lg, blocks, lds, st);
 }
 
 }  // namespace qsgd
