@@ -9,8 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqsgd.so")
-SOURCES = ["qsgd_capi.hip", "qsgd_encode.hip", "qsgd_decode.hip"]
-HEADERS = ["qsgd_device.hpp", "qsgd_kernels.hpp"]
+SOURCES = ["qsgd_capi.hip", "qsgd_encode.hip", "qsgd_decode.hip", "qsgd_general.hip"]
+HEADERS = ["qsgd_device.hpp", "qsgd_kernels.hpp", "qsgd_encode_wave.hpp"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -53,6 +53,34 @@ struct Geometry {
   bool bucket_path() const { return n > 0 && d % 4 == 0 && d <= kMaxBucketFast; }
 };
 
+// General path (any d): segments of kSeg values, workspace layout.
+struct GenPlan {
+  uint64_t spb, nseg;
+  uint32_t sub_words;
+  uint64_t off_partial, off_scale, off_seginfo, off_segstart, off_seggap, off_slots;
+  uint64_t enc_bytes;   // encode scratch (after the status block)
+  uint64_t dec_bytes;   // decode scratch: dense accumulator
+};
+
+uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+void plan_general(const Geometry& g, GenPlan& pl) {
+  pl.spb = (g.d + kSeg - 1) / kSeg;
+  pl.nseg = g.nb * pl.spb;
+  const uint64_t sub_bits = (uint64_t)kSeg * g.per_elem;
+  pl.sub_words = (uint32_t)(((sub_bits + 31) / 32 + 2 + 1) & ~(uint64_t)1);
+  uint64_t o = 0;
+  pl.off_partial = o; o = align_up(o + 8 * pl.nseg, 256);
+  pl.off_scale = o; o = align_up(o + 4 * g.nb, 256);
+  pl.off_seginfo = o; o = align_up(o + 12 * pl.nseg, 256);
+  pl.off_segstart = o; o = align_up(o + 8 * pl.nseg, 256);
+  pl.off_seggap = o; o = align_up(o + 4 * pl.nseg, 256);
+  pl.off_slots = o;
+  if (g.code != QSGD_CODE_FIXED) o = align_up(o + 4 * pl.nseg * pl.sub_words, 256);
+  pl.enc_bytes = o;
+  pl.dec_bytes = g.code == QSGD_CODE_FIXED ? 0 : align_up(4 * g.n, 256);
+}
+
 int make_geometry(const qsgd_params* p, Geometry& g) {
   if (!p) return QSGD_ERR_INVALID_ARG;
   if (p->s < 1 || p->s > 65535 || p->d < 1 || p->n > 0xFFFFFFFFull ||
@@ -182,9 +210,21 @@ int run_decode(const qsgd_params* p, const void* const* msgs_dev, const size_t* 
     if (launch_decode_check(a, st) != hipSuccess) return QSGD_ERR_HIP;
   }
   if (g.n == 0) return QSGD_OK;
-  if (!g.bucket_path()) return QSGD_ERR_UNSUPPORTED;
-
   const uint32_t cus = (uint32_t)device_cus();
+  if (!g.bucket_path()) {
+    const uint32_t blocks = (uint32_t)std::min<uint64_t>((g.n + 255) / 256, (uint64_t)cus * 32);
+    ScopedTiming tm("decode_general", st);
+    if (g.code == QSGD_CODE_FIXED) {
+      if (launch_gen_decode_fixed(a, blocks, st) != hipSuccess) return QSGD_ERR_HIP;
+      return QSGD_OK;
+    }
+    float* acc = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + kStatusBytes + kTotalsBytes);
+    if (launch_gen_zero(acc, g.n, blocks, st) != hipSuccess) return QSGD_ERR_HIP;
+    if (launch_gen_parse(a, acc, st) != hipSuccess) return QSGD_ERR_HIP;
+    if (launch_gen_apply(a, acc, blocks, st) != hipSuccess) return QSGD_ERR_HIP;
+    return QSGD_OK;
+  }
+
   if (g.code == QSGD_CODE_FIXED) {
     const uint32_t blocks = (uint32_t)std::min<uint64_t>((g.nb + 3) / 4, (uint64_t)cus * 16);
     ScopedTiming tm("decode_fixed", st);
@@ -234,7 +274,11 @@ size_t qsgd_workspace_bytes(const qsgd_params* p, uint32_t K) {
   Geometry g;
   if (make_geometry(p, g) || K > QSGD_MAX_PEERS) return 0;
   uint64_t bytes = kStatusBytes + kTotalsBytes;
-  if (g.bucket_path() && g.code != QSGD_CODE_FIXED) {
+  if (g.n > 0 && !g.bucket_path()) {
+    GenPlan gp;
+    plan_general(g, gp);
+    bytes += std::max(gp.enc_bytes, gp.dec_bytes);
+  } else if (g.bucket_path() && g.code != QSGD_CODE_FIXED) {
     // teams * bper < nb + teams, teams <= min(nb, kMaxTeams)
     const uint64_t slots = g.nb + std::min<uint64_t>(g.nb, kMaxTeams);
     bytes += slots * (g.max_words(g.d) + 4) * 4;
@@ -265,7 +309,45 @@ int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t 
       return QSGD_ERR_HIP;
     return QSGD_OK;
   }
-  if (!g.bucket_path()) return QSGD_ERR_UNSUPPORTED;
+  if (!g.bucket_path()) {
+    GenPlan gp;
+    plan_general(g, gp);
+    if (gp.nseg > 0x7FFFFFFFull) return QSGD_ERR_UNSUPPORTED;
+    if (workspace_bytes < kStatusBytes + kTotalsBytes + gp.enc_bytes) return QSGD_ERR_CAPACITY;
+    if (g.code == QSGD_CODE_FIXED && cap_words < g.max_payload_words()) return QSGD_ERR_CAPACITY;
+    uint8_t* wsb = static_cast<uint8_t*>(workspace_dev) + kStatusBytes + kTotalsBytes;
+    GenArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.g = g_dev; a.n = g.n; a.d = g.d; a.nb = g.nb; a.spb = gp.spb; a.nseg = gp.nseg;
+    a.s = g.s; a.code = g.code; a.norm_mode = g.norm;
+    a.key0 = (uint32_t)p->seed; a.key1 = (uint32_t)(p->seed >> 32);
+    a.stream_id = p->stream_id; a.iteration = p->iteration;
+    a.sub_words = gp.sub_words;
+    a.header = header; a.table = table; a.payload = payload;
+    a.cap_words = cap_words; a.table_words = g.table_words;
+    a.partial = reinterpret_cast<double*>(wsb + gp.off_partial);
+    a.scale = reinterpret_cast<float*>(wsb + gp.off_scale);
+    a.seginfo = reinterpret_cast<uint32_t*>(wsb + gp.off_seginfo);
+    a.segstart = reinterpret_cast<uint64_t*>(wsb + gp.off_segstart);
+    a.seggap = reinterpret_cast<uint32_t*>(wsb + gp.off_seggap);
+    a.slots = reinterpret_cast<uint32_t*>(wsb + gp.off_slots);
+    a.fixed_bits = g.fixed_bits;
+    a.fixed_words_full = g.max_words(g.d);
+    a.fixed_payload_words = g.code == QSGD_CODE_FIXED ? g.max_payload_words() : 0;
+    const bool aligned = g.d % 4 == 0;
+    ScopedTiming tm("encode_general", st);
+    if (launch_gen_partial(a, st) != hipSuccess) return QSGD_ERR_HIP;
+    if (launch_gen_scale(a, st) != hipSuccess) return QSGD_ERR_HIP;
+    if (launch_gen_encode(a, aligned, st) != hipSuccess) return QSGD_ERR_HIP;
+    if (g.code != QSGD_CODE_FIXED) {
+      if (launch_gen_scan(a, st) != hipSuccess) return QSGD_ERR_HIP;
+      const uint32_t fill_blocks =
+          (uint32_t)std::min<uint64_t>(std::max<uint64_t>(1, (cap_words + 2047) / 2048), 4096);
+      if (launch_gen_fill(a, fill_blocks, st) != hipSuccess) return QSGD_ERR_HIP;
+      if (launch_gen_place(a, st) != hipSuccess) return QSGD_ERR_HIP;
+    }
+    return QSGD_OK;
+  }
 
   EncodePlan pl;
   int tw, cpw;

@@ -18,10 +18,6 @@ namespace qsgd {
 
 namespace {
 
-__device__ __forceinline__ void flag_corrupt(uint32_t* status) {
-  atomicExch(status, (uint32_t)QSGD_ERR_CORRUPT);
-}
-
 // Recursive Elias code (App. A.2), decoder rule unrolled: N = 1; a 0 bit outputs N,
 // a 1 bit opens an (N+1)-bit group whose value is the new N.  `w` holds the next
 // 32 stream bits, first bit on top.  G = most groups accepted (G = 1: k <= 3,

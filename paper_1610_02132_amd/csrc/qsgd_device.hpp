@@ -129,6 +129,11 @@ __device__ __forceinline__ uint32_t lane_bcast(uint32_t v, int src) {
   return (uint32_t)__builtin_amdgcn_readlane((int)v, src);
 }
 
+// Records "a message did not parse / did not match" in a status word.
+__device__ __forceinline__ void flag_corrupt(uint32_t* status) {
+  atomicExch(status, 0xFFFFFFFDu);  // QSGD_ERR_CORRUPT (-3)
+}
+
 // Width of the fixed-width level field: narrowest of 2/4/8/16 bits holding
 // 0..s-1 (L2 scale: level s goes to the bucket's escape word) or 0..s (max scale).
 __host__ __device__ inline uint32_t fixed_field_bits(uint32_t s, uint32_t norm_mode) {

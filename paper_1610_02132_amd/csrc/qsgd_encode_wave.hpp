@@ -40,6 +40,32 @@ __device__ __forceinline__ uint32_t bits_below(uint64_t mask) {
                                    __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
+// The four draw words of the elements gidx .. gidx+3.  ALIGNED: gidx is a multiple
+// of 4 and they are one Philox block; otherwise they straddle two blocks.
+template <bool ALIGNED>
+__device__ __forceinline__ void draw4(uint64_t gidx, const QuantCtx& q, uint32_t r[4]) {
+  const uint64_t quad = gidx >> 2;
+  philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), q.stream_id, q.iteration, q.key0, q.key1,
+                r);
+  if constexpr (!ALIGNED) {
+    const uint32_t sh = (uint32_t)(gidx & 3u);
+    if (sh) {
+      uint32_t r2[4];
+      const uint64_t q2 = quad + 1;
+      philox4x32_10((uint32_t)q2, (uint32_t)(q2 >> 32), q.stream_id, q.iteration, q.key0,
+                    q.key1, r2);
+      const uint32_t all[8] = {r[0], r[1], r[2], r[3], r2[0], r2[1], r2[2], r2[3]};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        uint32_t v = all[j + 1];
+        if (sh == 2) v = all[j + 2];
+        if (sh == 3) v = all[j + 3];
+        r[j] = v;
+      }
+    }
+  }
+}
+
 // Stage 2 on `take` (1..64) records starting at ring slot `head`.
 // WIDE: gaps may need more than 21 bits, emit gap and (sign, level) separately.
 template <bool WIDE>
@@ -86,10 +112,10 @@ __device__ __forceinline__ void sparse_flush(const uint32_t* ring, uint32_t head
 //   v[c]      lane's float4 of chunk c (zeros past the end of the data)
 //   nchunks   chunks that hold data (<= CPW)
 //   pos0      bucket position (0-based) of the wavefront's first value
-//   gidx0     global index of the wavefront's first value (multiple of 4)
+//   gidx0     global index of the wavefront's first value (ALIGNED: multiple of 4)
 //   ring      kRingWords words of LDS private to this wavefront
 //   sub       zero-initialised LDS words private to this wavefront
-template <int CPW, bool WIDE>
+template <int CPW, bool WIDE, bool ALIGNED = true>
 __device__ __forceinline__ void encode_sparse_wave(const float4 (&v)[CPW], int nchunks,
                                                    uint32_t pos0, uint64_t gidx0, int lane,
                                                    const QuantCtx& q, uint32_t* ring,
@@ -98,10 +124,8 @@ __device__ __forceinline__ void encode_sparse_wave(const float4 (&v)[CPW], int n
 #pragma unroll
   for (int c = 0; c < CPW; ++c) {
     if (c >= nchunks) break;
-    const uint64_t quad = (gidx0 >> 2) + (uint64_t)c * 64u + (uint64_t)lane;
     uint32_t r[4];
-    philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), q.stream_id, q.iteration, q.key0,
-                  q.key1, r);
+    draw4<ALIGNED>(gidx0 + (uint64_t)c * kChunk + (uint64_t)lane * 4u, q, r);
     const float ts[4] = {v[c].x * q.inv, v[c].y * q.inv, v[c].z * q.inv, v[c].w * q.inv};
     bool nz[4];
     uint64_t mk[4];
@@ -152,7 +176,7 @@ __device__ __forceinline__ void encode_sparse_wave(const float4 (&v)[CPW], int n
 
 // Code'_s sub-stream (App. A.3): every coordinate sends its sign and Elias(level+1).
 //   len_valid  values that exist in the wavefront's range (the rest is padding)
-template <int CPW>
+template <int CPW, bool ALIGNED = true>
 __device__ __forceinline__ void encode_dense_wave(const float4 (&v)[CPW], int nchunks,
                                                   uint32_t len_valid, uint64_t gidx0, int lane,
                                                   const QuantCtx& q, uint32_t* sub,
@@ -160,10 +184,8 @@ __device__ __forceinline__ void encode_dense_wave(const float4 (&v)[CPW], int nc
 #pragma unroll
   for (int c = 0; c < CPW; ++c) {
     if (c >= nchunks) break;
-    const uint64_t quad = (gidx0 >> 2) + (uint64_t)c * 64u + (uint64_t)lane;
     uint32_t r[4];
-    philox4x32_10((uint32_t)quad, (uint32_t)(quad >> 32), q.stream_id, q.iteration, q.key0,
-                  q.key1, r);
+    draw4<ALIGNED>(gidx0 + (uint64_t)c * kChunk + (uint64_t)lane * 4u, q, r);
     const float vv[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
     const uint32_t e0 = (uint32_t)c * kChunk + (uint32_t)lane * 4u;
     uint64_t code[4];

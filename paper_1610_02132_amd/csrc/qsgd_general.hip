@@ -1,0 +1,521 @@
+// General path: any bucket size d (d > 8192, d not a multiple of 4, d = n).
+//
+// Encode.  A bucket no longer fits one workgroup's registers, so it is cut into
+// segments of 2048 values, one wavefront each, and the steps that the bucket path
+// does inside a workgroup become kernels:
+//   partial  per-segment sum of squares (fp64) or max            -> workspace
+//   scale    per-bucket reduction of the partials, s/scale
+//   encode   per-segment sub-stream (same wavefront code as the bucket path, with
+//            code words wide enough for 32-bit gaps)              -> workspace slot
+//   scan     one workgroup walks the segments in order: which nonzero precedes a
+//            segment's first one (max-scan), the bit offset of every segment in
+//            its bucket string (sum-scan), the word offset of every bucket
+//   fill     zeroes the payload
+//   place    per segment: ORs gap code, sub-stream and stop bit into the payload
+// Decode.  One thread per string parses records and adds them to a dense fp32
+// accumulator in the workspace with atomics (with three or more peers hitting the
+// same coordinate the order of the fp32 additions is not fixed); a last kernel
+// applies the accumulator to x.
+#include "qsgd_device.hpp"
+#include "qsgd_encode_wave.hpp"
+#include "qsgd_kernels.hpp"
+
+namespace qsgd {
+
+namespace {
+
+constexpr int kSegChunks = 8;  // kSeg / kChunk
+
+struct SegRef {
+  uint64_t b;        // bucket
+  uint32_t j;        // segment within the bucket
+  uint64_t m;        // elements in the bucket
+  uint32_t pos0;     // bucket position of the segment's first element
+  uint32_t len;      // elements in the segment (0: past the end of a short bucket)
+  uint64_t gidx0;    // global index of its first element
+};
+
+__device__ __forceinline__ SegRef seg_ref(const GenArgs& a, uint64_t seg) {
+  SegRef r;
+  r.b = seg / a.spb;
+  r.j = (uint32_t)(seg - r.b * a.spb);
+  const uint64_t base = r.b * a.d;
+  r.m = min(a.d, a.n - base);
+  const uint64_t p0 = (uint64_t)r.j * kSeg;
+  r.pos0 = (uint32_t)p0;
+  r.len = p0 < r.m ? (uint32_t)min((uint64_t)kSeg, r.m - p0) : 0u;
+  r.gidx0 = base + p0;
+  return r;
+}
+
+// Lane's four values of chunk c of a segment; any alignment, zeros past the end.
+__device__ __forceinline__ float4 load_quad_any(const float* __restrict__ g, uint64_t gidx,
+                                                uint32_t e, uint32_t len) {
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float* p = g + gidx + e;
+  if (e + 3 < len && (((gidx + e) & 3u) == 0)) {
+    v = *reinterpret_cast<const float4*>(p);
+  } else {
+    if (e + 0 < len) v.x = p[0];
+    if (e + 1 < len) v.y = p[1];
+    if (e + 2 < len) v.z = p[2];
+    if (e + 3 < len) v.w = p[3];
+  }
+  return v;
+}
+
+// Inclusive scans over a 1024-thread workgroup (16 wavefronts).
+template <typename T, typename Op>
+__device__ __forceinline__ T block_incl_scan(T v, T identity, T* wave_tot, Op op) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const T t = __shfl_up(v, o, kWave);
+    if (lane >= o) v = op(v, t);
+  }
+  __syncthreads();
+  if (lane == 63) wave_tot[wave] = v;
+  __syncthreads();
+  T pre = identity;
+  for (int w = 0; w < wave; ++w) pre = op(pre, wave_tot[w]);
+  __syncthreads();
+  return op(pre, v);
+}
+
+struct OpSum { __device__ unsigned long long operator()(unsigned long long a, unsigned long long b) const { return a + b; } };
+struct OpMax { __device__ unsigned long long operator()(unsigned long long a, unsigned long long b) const { return a > b ? a : b; } };
+
+}  // namespace
+
+// ---- encode --------------------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void k_gen_partial(GenArgs a) {
+  const int lane = threadIdx.x & 63;
+  const uint64_t seg = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (seg >= a.nseg) return;
+  const SegRef r = seg_ref(a, seg);
+  double ss = 0.0;
+  float mx = 0.f;
+  for (int c = 0; c < kSegChunks; ++c) {
+    const uint32_t e = (uint32_t)c * kChunk + lane * 4;
+    if ((uint32_t)c * kChunk >= r.len) break;
+    const float4 v = load_quad_any(a.g, r.gidx0, e, r.len);
+    if (a.norm_mode == 0) {
+      ss = fma((double)v.x, (double)v.x, ss);
+      ss = fma((double)v.y, (double)v.y, ss);
+      ss = fma((double)v.z, (double)v.z, ss);
+      ss = fma((double)v.w, (double)v.w, ss);
+    } else {
+      mx = fmaxf(fmaxf(mx, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    }
+  }
+  if (a.norm_mode == 0) ss = wave_sum_f64(ss);
+  else ss = (double)wave_max_f32(mx);
+  if (lane == 0) a.partial[seg] = ss;
+}
+
+__global__ __launch_bounds__(256) void k_gen_scale(GenArgs a) {
+  const int lane = threadIdx.x & 63;
+  const uint64_t b = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    uint32_t* h = a.header;
+    h[H_MAGIC] = kMagic; h[H_VERSION] = 1; h[H_CODE] = a.code; h[H_NORM] = a.norm_mode;
+    h[H_S] = a.s; h[H_STREAM] = a.stream_id;
+    h[H_D_LO] = (uint32_t)a.d; h[H_D_HI] = (uint32_t)(a.d >> 32);
+    h[H_N_LO] = (uint32_t)a.n; h[H_N_HI] = (uint32_t)(a.n >> 32);
+    h[H_NB_LO] = (uint32_t)a.nb; h[H_NB_HI] = (uint32_t)(a.nb >> 32);
+    h[H_PW_LO] = (uint32_t)a.fixed_payload_words;
+    h[H_PW_HI] = (uint32_t)(a.fixed_payload_words >> 32);
+    h[H_STATUS] = 0; h[H_ITER] = a.iteration;
+  }
+  if (b >= a.nb) return;
+  double acc = 0.0;
+  for (uint64_t j = lane; j < a.spb; j += kWave) {
+    const double p = a.partial[b * a.spb + j];
+    acc = a.norm_mode == 0 ? acc + p : fmax(acc, p);
+  }
+  float scale;
+  if (a.norm_mode == 0) scale = (float)sqrt(wave_sum_f64(acc));
+  else scale = wave_max_f32((float)acc);
+  if (lane == 0) {
+    a.scale[b] = scale;
+    if (a.code == QSGD_CODE_FIXED) {
+      uint32_t* str = a.payload + b * a.fixed_words_full;
+      str[0] = __float_as_uint(scale);
+      str[1] = 0xFFFFFFFFu;
+    }
+  }
+}
+
+template <int CODE, bool ALIGNED>
+__global__ __launch_bounds__(64) void k_gen_encode(GenArgs a) {
+  extern __shared__ uint32_t smem[];
+  uint32_t* const sub = smem;
+  uint32_t* const ring = smem + a.sub_words;
+  const int lane = threadIdx.x;
+  const uint64_t seg = blockIdx.x;
+  const SegRef r = seg_ref(a, seg);
+  if (CODE != QSGD_CODE_FIXED) {
+    for (uint32_t j = lane; j < a.sub_words; j += kWave) sub[j] = 0;
+    __syncthreads();
+  }
+  WaveOut wo;
+  wo.first_pos = 0; wo.last_pos = 0; wo.bits = 0;
+  if (r.len) {
+    float4 v[kSegChunks];
+#pragma unroll
+    for (int c = 0; c < kSegChunks; ++c) {
+      v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if ((uint32_t)c * kChunk < r.len)
+        v[c] = load_quad_any(a.g, r.gidx0, (uint32_t)c * kChunk + lane * 4, r.len);
+    }
+    const float scale = a.scale[r.b];
+    QuantCtx qc;
+    qc.s_f = (float)a.s;
+    qc.inv = (scale > 0.f) ? qc.s_f / scale : 0.f;
+    qc.s = a.s; qc.key0 = a.key0; qc.key1 = a.key1;
+    qc.stream_id = a.stream_id; qc.iteration = a.iteration;
+    const int nchunks = (int)((r.len + kChunk - 1) / kChunk);
+    if (CODE == QSGD_CODE_SPARSE) {
+      encode_sparse_wave<kSegChunks, true, ALIGNED>(v, nchunks, r.pos0, r.gidx0, lane, qc, ring,
+                                                    sub, wo);
+    } else if (CODE == QSGD_CODE_DENSE) {
+      encode_dense_wave<kSegChunks, ALIGNED>(v, nchunks, r.len, r.gidx0, lane, qc, sub, wo);
+    } else {
+      // fixed width: fields of 2048 values start on word boundaries in both planes
+      const uint32_t B = a.fixed_bits, fmax = (1u << B) - 1u;
+      uint32_t* const str = a.payload + r.b * a.fixed_words_full;
+      const uint64_t lw = (r.m * B + 31) >> 5;
+      uint32_t* const lplane = str + 2 + (((uint64_t)r.pos0 * B) >> 5);
+      uint32_t* const splane = str + 2 + lw + (r.pos0 >> 5);
+      const uint32_t lwn = (uint32_t)((r.len * B + 31u) >> 5), swn = (r.len + 31u) >> 5;
+#pragma unroll
+      for (int c = 0; c < kSegChunks; ++c) {
+        if (c >= nchunks) break;
+        const uint32_t e0 = (uint32_t)c * kChunk + lane * 4;
+        uint32_t rr[4];
+        draw4<ALIGNED>(r.gidx0 + e0, qc, rr);
+        const float vv[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+        uint32_t z[4], nib = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          z[j] = (e0 + j < r.len) ? quantize_one(vv[j], qc.inv, qc.s_f, qc.s, rr[j]) : 0u;
+          if (z[j] > fmax) { str[1] = r.pos0 + e0 + j; z[j] = fmax; }
+          nib |= (vv[j] < 0.f ? 1u : 0u) << j;
+        }
+        if (B == 8) {
+          if ((e0 >> 2) < lwn) lplane[e0 >> 2] = z[0] | (z[1] << 8) | (z[2] << 16) | (z[3] << 24);
+        } else if (B == 16) {
+          if ((e0 >> 1) < lwn) lplane[e0 >> 1] = z[0] | (z[1] << 16);
+          if ((e0 >> 1) + 1 < lwn) lplane[(e0 >> 1) + 1] = z[2] | (z[3] << 16);
+        } else if (B == 4) {
+          uint32_t h = z[0] | (z[1] << 4) | (z[2] << 8) | (z[3] << 12);
+          h |= __shfl_down(h, 1, kWave) << 16;
+          if ((lane & 1) == 0 && (e0 >> 3) < lwn) lplane[e0 >> 3] = h;
+        } else {
+          uint32_t h = z[0] | (z[1] << 2) | (z[2] << 4) | (z[3] << 6);
+          h |= __shfl_down(h, 1, kWave) << 8;
+          h |= __shfl_down(h, 2, kWave) << 16;
+          if ((lane & 3) == 0 && (e0 >> 4) < lwn) lplane[e0 >> 4] = h;
+        }
+        uint32_t sg = nib;
+        sg |= __shfl_down(sg, 1, kWave) << 4;
+        sg |= __shfl_down(sg, 2, kWave) << 8;
+        sg |= __shfl_down(sg, 4, kWave) << 16;
+        if ((lane & 7) == 0 && (e0 >> 5) < swn) splane[e0 >> 5] = sg;
+      }
+    }
+  }
+  if (CODE == QSGD_CODE_FIXED) return;
+  __syncthreads();
+  if (lane == 0) {
+    a.seginfo[3 * seg + 0] = wo.first_pos;
+    a.seginfo[3 * seg + 1] = wo.last_pos;
+    a.seginfo[3 * seg + 2] = wo.bits;
+  }
+  uint32_t* slot = a.slots + seg * a.sub_words;
+  const uint32_t nw = (wo.bits + 31u) >> 5;
+  for (uint32_t j = lane; j < nw; j += kWave) slot[j] = sub[j];
+}
+
+// One workgroup of 1024 threads walks all segments in order.
+__global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
+  __shared__ unsigned long long wave_tot[16];
+  __shared__ unsigned long long tmp[1024];
+  __shared__ unsigned long long carry[3];  // max global position, bits in open bucket, words
+  const int i = threadIdx.x;
+  if (i == 0) { carry[0] = 0; carry[1] = 0; carry[2] = 0; a.table[0] = 0; }
+  __syncthreads();
+  const bool sparse = a.code == QSGD_CODE_SPARSE;
+  for (uint64_t c0 = 0; c0 < a.nseg; c0 += 1024) {
+    const uint64_t seg = c0 + i;
+    const bool live = seg < a.nseg;
+    uint64_t b = 0; uint32_t j = 0, first = 0, last = 0, bits = 0;
+    if (live) {
+      b = seg / a.spb; j = (uint32_t)(seg - b * a.spb);
+      first = a.seginfo[3 * seg]; last = a.seginfo[3 * seg + 1]; bits = a.seginfo[3 * seg + 2];
+    }
+    const unsigned long long base = b * a.d;
+    const unsigned long long c_max = carry[0], c_bits = carry[1], c_words = carry[2];
+    // which nonzero precedes this segment's first one
+    const unsigned long long lastg = (live && first) ? base + last : 0ull;
+    const unsigned long long m_incl = block_incl_scan<unsigned long long>(lastg, 0ull, wave_tot, OpMax());
+    tmp[i] = m_incl;
+    __syncthreads();
+    unsigned long long prevg = i ? tmp[i - 1] : 0ull;
+    prevg = prevg > c_max ? prevg : c_max;
+    const unsigned long long chunk_max = tmp[1023];
+    __syncthreads();
+    const uint32_t prev_in_bucket = prevg > base ? (uint32_t)(prevg - base) : 0u;
+    const uint32_t gap = (live && first && sparse) ? first - prev_in_bucket : 0u;
+    const uint32_t glen = gap ? omega_length(gap) : 0u;
+    const unsigned long long tb = (unsigned long long)glen + bits;
+    // bit offset of the segment inside its bucket string
+    const unsigned long long s_incl = block_incl_scan<unsigned long long>(tb, 0ull, wave_tot, OpSum());
+    const unsigned long long s_excl = s_incl - tb;
+    tmp[i] = s_excl;
+    __syncthreads();
+    unsigned long long before;  // bits of this bucket's records before this segment
+    if ((unsigned long long)j <= (unsigned long long)i) before = s_excl - tmp[i - j];
+    else before = c_bits + s_excl;
+    __syncthreads();
+    const bool is_end = live && j == a.spb - 1;
+    unsigned long long words = 0;
+    if (is_end) words = (32ull + before + tb + (sparse ? 1ull : 0ull) + 31ull) >> 5;
+    const unsigned long long w_incl = block_incl_scan<unsigned long long>(words, 0ull, wave_tot, OpSum());
+    if (live) {
+      a.segstart[seg] = 32ull + before;
+      a.seggap[seg] = gap;
+      if (is_end) {
+        const unsigned long long off = c_words + w_incl;
+        a.table[b + 1] = off > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)off;
+      }
+    }
+    __syncthreads();
+    if (live && (i == 1023 || seg == a.nseg - 1)) {
+      carry[0] = chunk_max > c_max ? chunk_max : c_max;
+      carry[1] = is_end ? 0ull : before + tb;
+      carry[2] = c_words + w_incl;
+    }
+    __syncthreads();
+  }
+  if (i == 0) {
+    const unsigned long long total = carry[2];
+    a.header[H_PW_LO] = (uint32_t)total;
+    a.header[H_PW_HI] = (uint32_t)(total >> 32);
+    for (uint64_t t = a.nb + 1; t < a.table_words; ++t) a.table[t] = 0;
+    if (total > a.cap_words || total > 0xFFFFFFFFull)
+      a.header[H_STATUS] = (uint32_t)QSGD_ERR_CAPACITY;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_gen_fill(GenArgs a) {
+  const uint64_t total = a.header[H_PW_LO] | ((uint64_t)a.header[H_PW_HI] << 32);
+  const uint64_t lim = min(total, a.cap_words);
+  for (uint64_t w = (uint64_t)blockIdx.x * 256 + threadIdx.x; w < lim; w += (uint64_t)gridDim.x * 256)
+    a.payload[w] = 0;
+}
+
+__global__ __launch_bounds__(64) void k_gen_place(GenArgs a) {
+  if (a.header[H_STATUS] != 0) return;  // does not fit: nothing is written
+  const int lane = threadIdx.x;
+  const uint64_t seg = blockIdx.x;
+  const uint64_t b = seg / a.spb;
+  const uint32_t j = (uint32_t)(seg - b * a.spb);
+  uint32_t* const str = a.payload + a.table[b];
+  const uint32_t bits = a.seginfo[3 * seg + 2];
+  const uint32_t gap = a.seggap[seg];
+  const uint64_t start = a.segstart[seg];
+  uint32_t glen = 0;
+  if (lane == 0) {
+    if (j == 0) str[0] = __float_as_uint(a.scale[b]);
+    if (gap) {
+      uint64_t gc;
+      omega_encode(gap, gc, glen);
+      global_emit(str, start, gc, glen);
+    }
+    if (j == a.spb - 1 && a.code == QSGD_CODE_SPARSE) global_emit(str, start + glen + bits, 1ull, 1u);
+  }
+  glen = lane_bcast(glen, 0);
+  const uint64_t o = start + glen;
+  const uint64_t w0 = o >> 5;
+  const uint32_t sh = (uint32_t)(o & 31u);
+  const uint32_t* slot = a.slots + seg * a.sub_words;
+  const uint32_t nw = (bits + 31u) >> 5;
+  for (uint32_t t = lane; t < nw; t += kWave) {
+    const uint32_t x = slot[t];
+    if (x) {
+      atomicOr(&str[w0 + t], x >> sh);
+      if (sh && (x << (32u - sh))) atomicOr(&str[w0 + t + 1], x << (32u - sh));
+    }
+  }
+}
+
+// ---- decode --------------------------------------------------------------------------
+
+namespace {
+
+// 64 stream bits starting at bit `bitpos` of a string of nwords words (zeros past the end).
+__device__ __forceinline__ uint64_t peek64(const uint32_t* w, uint64_t nwords, uint64_t bitpos) {
+  const uint64_t wi = bitpos >> 5;
+  const uint32_t off = (uint32_t)(bitpos & 31u);
+  const uint64_t a0 = wi < nwords ? w[wi] : 0u;
+  const uint64_t a1 = wi + 1 < nwords ? w[wi + 1] : 0u;
+  const uint64_t a2 = wi + 2 < nwords ? w[wi + 2] : 0u;
+  const uint64_t hi = (a0 << 32) | a1;
+  return off ? (hi << off) | (a2 >> (32u - off)) : hi;
+}
+
+// Decoder rule of the recursive Elias code (App. A.2) on a 64-bit window; values
+// below 2^32.  Returns 0 for malformed input; `len` = bits used.
+__device__ __forceinline__ uint32_t omega_loop(uint64_t w, uint32_t& len) {
+  uint32_t N = 1, used = 0;
+  for (;;) {
+    if ((w >> 63) == 0) { len = used + 1; return N; }
+    if (N > 31u || used + N + 2u > 64u) { len = 0; return 0; }
+    const uint32_t v = (uint32_t)(w >> (63u - N));
+    w <<= (N + 1u);
+    used += N + 1u;
+    N = v;
+  }
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(256) void k_gen_zero(float* p, uint64_t n) {
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)gridDim.x * 256)
+    p[i] = 0.f;
+}
+
+__global__ __launch_bounds__(256) void k_gen_parse(DecodeArgs a, float* acc) {
+  if (*a.status != 0) return;
+  const uint64_t idx = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (uint64_t)a.nb * a.K) return;
+  const uint64_t b = idx / a.K;
+  const uint32_t k = (uint32_t)(idx - b * a.K);
+  const uint64_t base = b * (uint64_t)a.d;
+  const uint64_t m = min((uint64_t)a.d, a.n - base);
+  const uint32_t* msg = a.msgs[k];
+  const uint64_t pay = (uint64_t)H_WORDS + a.table_words;
+  const uint32_t o0 = msg[H_WORDS + b], o1 = msg[H_WORDS + b + 1];
+  if (!(o0 < o1 && pay + o1 <= a.msg_words[k])) { flag_corrupt(a.status); return; }
+  const uint32_t* str = msg + pay + o0;
+  const uint64_t nwords = o1 - o0;
+  const float scale = __uint_as_float(str[0]) / (float)a.s;
+  uint64_t endbit = nwords * 32;
+  const bool sparse = a.code == QSGD_CODE_SPARSE;
+  if (sparse) {
+    const uint32_t last = str[nwords - 1];
+    if (last == 0) { flag_corrupt(a.status); return; }
+    endbit = nwords * 32 - 1 - (uint32_t)(__ffs((int)last) - 1);
+    if (endbit < 32) { flag_corrupt(a.status); return; }
+  }
+  uint64_t bitpos = 32, pos = 0;
+  float* out = acc + base;
+  for (;;) {
+    if (sparse ? bitpos >= endbit : pos >= m) break;
+    uint32_t gl = 0, gap = 1;
+    if (sparse) {
+      gap = omega_loop(peek64(str, nwords, bitpos), gl);
+      if (gap == 0) { flag_corrupt(a.status); return; }
+    }
+    const uint64_t w = peek64(str, nwords, bitpos + gl);
+    uint32_t ll;
+    uint32_t lev = omega_loop(w << 1, ll);
+    bitpos += gl + 1u + ll;
+    pos += gap;
+    if (lev == 0 || pos > m || bitpos > endbit) { flag_corrupt(a.status); return; }
+    if (!sparse) lev -= 1u;
+    if (lev > a.s) { flag_corrupt(a.status); return; }
+    if (lev) {
+      const float mag = scale * (float)lev;
+      atomicAdd(&out[pos - 1], (w >> 63) ? -mag : mag);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_gen_apply(DecodeArgs a, const float* acc) {
+  if (*a.status != 0) return;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < a.n; i += (uint64_t)gridDim.x * 256)
+    a.x[i] = a.step ? fmaf(-a.c, acc[i], a.x[i]) : a.x[i] + acc[i];
+}
+
+// Fixed width, any bucket size: one thread per coordinate, peers summed in order.
+__global__ __launch_bounds__(256) void k_gen_decode_fixed(DecodeArgs a) {
+  if (*a.status != 0) return;
+  const uint32_t B = a.fixed_bits, fmask = (1u << B) - 1u;
+  const float s_f = (float)a.s;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < a.n; i += (uint64_t)gridDim.x * 256) {
+    const uint64_t b = i / (uint64_t)a.d;
+    const uint64_t e = i - b * (uint64_t)a.d;
+    const uint64_t m = min((uint64_t)a.d, a.n - b * (uint64_t)a.d);
+    const uint64_t lw = (m * B + 31) >> 5, sw = (m + 31) >> 5;
+    const uint64_t off = (uint64_t)H_WORDS + b * (uint64_t)a.fixed_words_full;
+    float sum = 0.f;
+    for (uint32_t k = 0; k < a.K; ++k) {
+      if (off + 2 + lw + sw > a.msg_words[k]) { flag_corrupt(a.status); continue; }
+      const uint32_t* str = a.msgs[k] + off;
+      uint32_t z = (str[2 + ((e * B) >> 5)] >> ((e * B) & 31u)) & fmask;
+      if (str[1] == (uint32_t)e) z = a.s;
+      if (z > a.s) { flag_corrupt(a.status); z = 0; }
+      const uint32_t neg = (str[2 + lw + (e >> 5)] >> (e & 31u)) & 1u;
+      const float mag = (__uint_as_float(str[0]) / s_f) * (float)z;
+      sum += (z && neg) ? -mag : mag;
+    }
+    a.x[i] = a.step ? fmaf(-a.c, sum, a.x[i]) : a.x[i] + sum;
+  }
+}
+
+// ---- launchers -------------------------------------------------------------------------
+
+hipError_t launch_gen_partial(const GenArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(k_gen_partial, dim3((uint32_t)((a.nseg + 3) / 4)), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+hipError_t launch_gen_scale(const GenArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(k_gen_scale, dim3((uint32_t)((a.nb + 3) / 4)), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+hipError_t launch_gen_encode(const GenArgs& a, bool aligned, hipStream_t st) {
+  const dim3 grid((uint32_t)a.nseg), block(64);
+  const size_t lds = 4 * ((size_t)a.sub_words + kRingWords);
+#define QSGD_GEN(CODE)                                                                       \
+  if (aligned) hipLaunchKernelGGL((k_gen_encode<CODE, true>), grid, block, lds, st, a);      \
+  else hipLaunchKernelGGL((k_gen_encode<CODE, false>), grid, block, lds, st, a)
+  if (a.code == QSGD_CODE_SPARSE) { QSGD_GEN(QSGD_CODE_SPARSE); }
+  else if (a.code == QSGD_CODE_DENSE) { QSGD_GEN(QSGD_CODE_DENSE); }
+  else { QSGD_GEN(QSGD_CODE_FIXED); }
+#undef QSGD_GEN
+  return hipGetLastError();
+}
+hipError_t launch_gen_scan(const GenArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(k_gen_scan, dim3(1), dim3(1024), 0, st, a);
+  return hipGetLastError();
+}
+hipError_t launch_gen_fill(const GenArgs& a, uint32_t blocks, hipStream_t st) {
+  hipLaunchKernelGGL(k_gen_fill, dim3(blocks), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+hipError_t launch_gen_place(const GenArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(k_gen_place, dim3((uint32_t)a.nseg), dim3(64), 0, st, a);
+  return hipGetLastError();
+}
+hipError_t launch_gen_zero(float* p, uint64_t n, uint32_t blocks, hipStream_t st) {
+  hipLaunchKernelGGL(k_gen_zero, dim3(blocks), dim3(256), 0, st, p, n);
+  return hipGetLastError();
+}
+hipError_t launch_gen_parse(const DecodeArgs& a, float* acc, hipStream_t st) {
+  const uint64_t strings = (uint64_t)a.nb * a.K;
+  hipLaunchKernelGGL(k_gen_parse, dim3((uint32_t)((strings + 255) / 256)), dim3(256), 0, st, a, acc);
+  return hipGetLastError();
+}
+hipError_t launch_gen_apply(const DecodeArgs& a, const float* acc, uint32_t blocks, hipStream_t st) {
+  hipLaunchKernelGGL(k_gen_apply, dim3(blocks), dim3(256), 0, st, a, acc);
+  return hipGetLastError();
+}
+hipError_t launch_gen_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t st) {
+  hipLaunchKernelGGL(k_gen_decode_fixed, dim3(blocks), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace qsgd

@@ -74,6 +74,34 @@ struct DecodeArgs {
   uint32_t fixed_words_full;
 };
 
+constexpr uint32_t kSeg = 2048;  // values per segment on the general path
+
+struct GenArgs {
+  const float* g;
+  uint64_t n, d, nb;
+  uint64_t spb;        // segments per bucket
+  uint64_t nseg;       // nb * spb
+  uint32_t s, code, norm_mode;
+  uint32_t key0, key1, stream_id, iteration;
+  uint32_t sub_words;  // words of one segment's sub-stream slot (even)
+  uint32_t* header;
+  uint32_t* table;
+  uint32_t* payload;
+  uint64_t cap_words;
+  uint64_t table_words;
+  // workspace
+  double* partial;     // nseg: sum of squares (or max) of each segment
+  float* scale;        // nb
+  uint32_t* seginfo;   // 3 * nseg: first position, last position, bits
+  uint64_t* segstart;  // nseg: bit offset of the segment's gap code in its bucket string
+  uint32_t* seggap;    // nseg: gap in front of the segment's first record (0: none)
+  uint32_t* slots;     // nseg * sub_words
+  // fixed width
+  uint32_t fixed_bits;
+  uint64_t fixed_words_full;
+  uint64_t fixed_payload_words;
+};
+
 hipError_t launch_encode_bucket(const EncodeArgs& a, uint32_t code, int tw, int cpw,
                                 uint32_t teams, size_t lds, hipStream_t st);
 hipError_t launch_encode_compact(const CompactArgs& a, uint32_t teams, hipStream_t st);
@@ -84,5 +112,16 @@ hipError_t launch_write_empty(uint32_t* header, uint32_t* table, uint32_t code, 
 hipError_t launch_decode_check(const DecodeArgs& a, hipStream_t st);
 hipError_t launch_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t st);
 hipError_t launch_decode_elias(const DecodeArgs& a, uint32_t blocks, size_t lds, hipStream_t st);
+
+hipError_t launch_gen_partial(const GenArgs& a, hipStream_t st);
+hipError_t launch_gen_scale(const GenArgs& a, hipStream_t st);
+hipError_t launch_gen_encode(const GenArgs& a, bool aligned, hipStream_t st);
+hipError_t launch_gen_scan(const GenArgs& a, hipStream_t st);
+hipError_t launch_gen_fill(const GenArgs& a, uint32_t blocks, hipStream_t st);
+hipError_t launch_gen_place(const GenArgs& a, hipStream_t st);
+hipError_t launch_gen_zero(float* p, uint64_t n, uint32_t blocks, hipStream_t st);
+hipError_t launch_gen_parse(const DecodeArgs& a, float* acc, hipStream_t st);
+hipError_t launch_gen_apply(const DecodeArgs& a, const float* acc, uint32_t blocks, hipStream_t st);
+hipError_t launch_gen_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t st);
 
 }  // namespace qsgd

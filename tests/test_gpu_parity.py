@@ -56,6 +56,26 @@ def test_bucket_sizes(d, code):
     run_case(w)
 
 
+GENERAL = [  # d > 8192, d not a multiple of 4, d = n: the segmented path
+    (W.scaled(W.C4, 200_003), None),                                             # s=1, one bucket of n
+    (W.Workload("g10000", 10000 * 7 + 4321, 4, 10000, q.CODE_SPARSE, 3, 0.1, "normal_outliers", (74321,)), None),
+    (W.Workload("g8196", 8196 * 5 + 100, 16, 8196, q.CODE_SPARSE, 8, 0.1, "laplace_lognormal", (20000, 21080)), None),
+    (W.Workload("g130", 130 * 301 + 77, 4, 130, q.CODE_SPARSE, 4, 0.1, "normal", (130 * 301 + 77,)), None),
+    (W.Workload("g1", 333, 7, 1, q.CODE_SPARSE, 2, 0.1, "normal", (333,)), None),
+    (W.Workload("g9999", 9999 * 4 + 5, 3, 9999, q.CODE_SPARSE, 5, 0.1, "student_t", (40001,)), None),
+    (W.Workload("g70001", 70001, 256, 70001, q.CODE_SPARSE, 2, 0.1, "normal", (70001,)), None),
+]
+
+
+@pytest.mark.parametrize("w", [g[0] for g in GENERAL], ids=lambda w: w.name)
+@pytest.mark.parametrize("code", [q.CODE_SPARSE, q.CODE_DENSE, q.CODE_FIXED])
+def test_general_path(w, code):
+    # the Elias decode of this path sums with atomics: bit-exactness is not required of it
+    run_case(w, code=code, expect_exact_step=(code == q.CODE_FIXED))
+    if code == q.CODE_SPARSE:
+        run_case(w, code=code, norm=q.NORM_MAX, expect_exact_step=False)
+
+
 @pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 16, 17, 255, 256, 1000, 65535])
 @pytest.mark.parametrize("code", [q.CODE_SPARSE, q.CODE_DENSE, q.CODE_FIXED])
 def test_levels(s, code):
