@@ -103,7 +103,8 @@ def gradient(w: Workload, k: int, device="cpu", base_seed: int = 1234) -> torch.
             seg.normal_(0.0, 1e-3, generator=gen)
         elif w.dist == "laplace_lognormal":
             scale = math.exp(float(torch.randn((), generator=cg)) * 1.5 - 7.0)
-            u = torch.rand(size, generator=gen, device=dev) - 0.5
+            # inverse CDF of Laplace(0, 1); the draw is kept off 0 so the log stays finite
+            u = torch.rand(size, generator=gen, device=dev).clamp_(1e-7, 1.0 - 1e-7) - 0.5
             seg.copy_(-scale * torch.sign(u) * torch.log1p(-2.0 * u.abs()))
         elif w.dist == "normal_loguniform":
             e = float(torch.rand((), generator=cg)) * 3.0 - 5.0  # sigma in [1e-5, 1e-2]
@@ -122,7 +123,7 @@ def gradient(w: Workload, k: int, device="cpu", base_seed: int = 1234) -> torch.
                 part = seg[c0:c1]
                 part.normal_(0.0, 1e-3, generator=gen)
                 hit = torch.rand(c1 - c0, generator=gen, device=dev) < 1e-3
-                part[hit] *= 100.0
+                part.mul_(torch.where(hit, 100.0, 1.0))
         else:
             raise ValueError(w.dist)
         off += size
