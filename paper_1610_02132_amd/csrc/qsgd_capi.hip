@@ -352,7 +352,7 @@ int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t 
   EncodePlan pl;
   int tw, cpw;
   team_shape(g.d, tw, cpw);
-  const uint32_t target = std::min<uint32_t>(kMaxTeams, (uint32_t)device_cus() * (16u / tw));
+  const uint32_t target = std::min<uint32_t>(kMaxTeams, (uint32_t)device_cus() * (32u / tw));
   plan_encode(g, target, pl);
   if (workspace_bytes < kStatusBytes + pl.ws_bytes) return QSGD_ERR_CAPACITY;
   if (g.code == QSGD_CODE_FIXED && cap_words < g.max_payload_words()) return QSGD_ERR_CAPACITY;

@@ -102,82 +102,114 @@ __global__ void k_decode_check(DecodeArgs a) {
 }
 
 // ---- fixed width: one wavefront per bucket ----------------------------------------
+// Lane k < K keeps message k's scale and escape index.  The level and sign words of
+// KG messages are requested together so that enough bytes are in flight per
+// wavefront; the sum over the messages runs in k order in registers.
+constexpr int kFixedGroup = 8;
+
+template <int B>
 __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
   if (*a.status != 0) return;
   const int lane = threadIdx.x & 63;
   const uint32_t wave_global = blockIdx.x * 4 + (threadIdx.x >> 6);
   const uint32_t wave_count = gridDim.x * 4;
-  const uint32_t B = a.fixed_bits, s = a.s;
+  const uint32_t s = a.s, K = a.K;
   const float s_f = (float)s;
-  const uint32_t fmask = (1u << B) - 1u;
+  constexpr uint32_t fmask = (1u << B) - 1u;
+  constexpr int LW = B == 16 ? 2 : 1;       // level words a lane reads per message
+  const bool check_range = fmask > s;       // a field can hold a level above s
 
   for (uint32_t b = wave_global; b < a.nb; b += wave_count) {
     const uint64_t base = (uint64_t)b * a.d;
     const uint32_t m = (uint32_t)min((uint64_t)a.d, a.n - base);
     const uint32_t lw = (m * B + 31u) >> 5, sw = (m + 31u) >> 5;
     const uint64_t str_off = (uint64_t)H_WORDS + (uint64_t)b * a.fixed_words_full;
-    // lane k < K holds the scale and the escape index of message k's string
     float my_scale = 0.f;
     uint32_t my_esc = 0xFFFFFFFFu, my_ok = 0;
-    if ((uint32_t)lane < a.K) {
+    if ((uint32_t)lane < K) {
       if (str_off + 2u + lw + sw <= a.msg_words[lane]) {
         const uint32_t* str = a.msgs[lane] + str_off;
         my_scale = __uint_as_float(str[0]) / s_f;
         my_esc = str[1];
-        my_ok = 1;
-        if (my_esc != 0xFFFFFFFFu && my_esc >= m) { my_ok = 0; }
+        my_ok = (my_esc == 0xFFFFFFFFu || my_esc < m) ? 1u : 0u;
       }
-      if (!my_ok) flag_corrupt(a.status);
+      if (!my_ok) { flag_corrupt(a.status); my_scale = 0.f; my_esc = 0xFFFFFFFFu; }
     }
+    const uint64_t okmask = __ballot(my_ok != 0);
     for (uint32_t e0 = lane * 4; e0 < m; e0 += kChunk) {
+      float* xp = a.x + base + e0;
+      const bool full = e0 + 3 < m;
+      float4 xv = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (full) {
+        xv = *reinterpret_cast<const float4*>(xp);
+      } else {
+        xv.x = xp[0];
+        if (e0 + 1 < m) xv.y = xp[1];
+        if (e0 + 2 < m) xv.z = xp[2];
+      }
       float acc[4] = {0.f, 0.f, 0.f, 0.f};
-      for (uint32_t k = 0; k < a.K; ++k) {
-        if (!lane_bcast(my_ok, k)) continue;
-        const float sc = __uint_as_float(lane_bcast(__float_as_uint(my_scale), k));
-        const uint32_t esc = lane_bcast(my_esc, k);
-        const uint32_t* lplane = a.msgs[k] + str_off + 2;
-        const uint32_t* splane = lplane + lw;
-        uint32_t z[4];
-        if (B == 8) {
-          const uint32_t w = lplane[e0 >> 2];
-          z[0] = w & 0xFFu; z[1] = (w >> 8) & 0xFFu; z[2] = (w >> 16) & 0xFFu; z[3] = w >> 24;
-        } else if (B == 16) {
-          const uint32_t w0 = lplane[e0 >> 1];
-          const uint32_t w1 = ((e0 >> 1) + 1 < lw) ? lplane[(e0 >> 1) + 1] : 0u;
-          z[0] = w0 & 0xFFFFu; z[1] = w0 >> 16; z[2] = w1 & 0xFFFFu; z[3] = w1 >> 16;
-        } else {
-          const uint32_t w = lplane[(e0 * B) >> 5] >> ((e0 * B) & 31u);
-          z[0] = w & fmask; z[1] = (w >> B) & fmask; z[2] = (w >> (2 * B)) & fmask;
-          z[3] = (w >> (3 * B)) & fmask;
-        }
-        const uint32_t sg = splane[e0 >> 5] >> (e0 & 31u);
+      const uint32_t li = (e0 * B) >> 5, si = e0 >> 5, ssh = e0 & 31u;
+      for (uint32_t k0 = 0; k0 < K; k0 += kFixedGroup) {
+        uint32_t wl[kFixedGroup][LW], ws[kFixedGroup];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          if (esc == e0 + j) z[j] = s;
-        bool bad = false;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (e0 + j < m) {
-            bad |= z[j] > s;
-            const float mag = sc * (float)z[j];
-            acc[j] += (z[j] != 0 && ((sg >> j) & 1u)) ? -mag : mag;
+        for (int t = 0; t < kFixedGroup; ++t) {
+          const uint32_t k = k0 + t;
+          wl[t][0] = 0; ws[t] = 0;
+          if (LW == 2) wl[t][LW - 1] = 0;
+          if (k < K && ((okmask >> k) & 1ull)) {
+            const uint32_t* lplane = a.msgs[k] + str_off + 2;
+            wl[t][0] = lplane[li];
+            if (LW == 2 && li + 1 < lw) wl[t][LW - 1] = lplane[li + 1];
+            ws[t] = lplane[lw + si];
           }
         }
-        if (bad) flag_corrupt(a.status);
-      }
-      float* xp = a.x + base + e0;
-      if (e0 + 3 < m) {
-        float4 xv = *reinterpret_cast<float4*>(xp);
-        if (a.step) {
-          xv.x = fmaf(-a.c, acc[0], xv.x); xv.y = fmaf(-a.c, acc[1], xv.y);
-          xv.z = fmaf(-a.c, acc[2], xv.z); xv.w = fmaf(-a.c, acc[3], xv.w);
-        } else {
-          xv.x += acc[0]; xv.y += acc[1]; xv.z += acc[2]; xv.w += acc[3];
+#pragma unroll
+        for (int t = 0; t < kFixedGroup; ++t) {
+          const uint32_t k = k0 + t;
+          if (k >= K) break;
+          const float sc = __uint_as_float(lane_bcast(__float_as_uint(my_scale), (int)k));
+          const uint32_t esc = lane_bcast(my_esc, (int)k);
+          uint32_t z[4];
+          if (B == 8) {
+            z[0] = wl[t][0] & 0xFFu; z[1] = (wl[t][0] >> 8) & 0xFFu;
+            z[2] = (wl[t][0] >> 16) & 0xFFu; z[3] = wl[t][0] >> 24;
+          } else if (B == 16) {
+            z[0] = wl[t][0] & 0xFFFFu; z[1] = wl[t][0] >> 16;
+            z[2] = wl[t][LW - 1] & 0xFFFFu; z[3] = wl[t][LW - 1] >> 16;
+          } else {
+            const uint32_t w = wl[t][0] >> ((e0 * B) & 31u);
+            z[0] = w & fmask; z[1] = (w >> B) & fmask; z[2] = (w >> (2 * B)) & fmask;
+            z[3] = (w >> (3 * B)) & fmask;
+          }
+          if (esc != 0xFFFFFFFFu) {  // wave-uniform: this message has a top-level value here
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (esc == e0 + j) z[j] = s;
+          }
+          if (check_range) {
+            if (z[0] > s || z[1] > s || z[2] > s || z[3] > s) flag_corrupt(a.status);
+          }
+          const uint32_t sg = ws[t] >> ssh;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            // sign bit into the product: (-0 for a zero level adds like +0)
+            const uint32_t mag = __float_as_uint(sc * (float)z[j]);
+            acc[j] += __uint_as_float(mag ^ ((sg << (31 - j)) & 0x80000000u));
+          }
         }
+      }
+      if (a.step) {
+        xv.x = fmaf(-a.c, acc[0], xv.x); xv.y = fmaf(-a.c, acc[1], xv.y);
+        xv.z = fmaf(-a.c, acc[2], xv.z); xv.w = fmaf(-a.c, acc[3], xv.w);
+      } else {
+        xv.x += acc[0]; xv.y += acc[1]; xv.z += acc[2]; xv.w += acc[3];
+      }
+      if (full) {
         *reinterpret_cast<float4*>(xp) = xv;
       } else {
-        for (int j = 0; j < 4; ++j)
-          if (e0 + j < m) xp[j] = a.step ? fmaf(-a.c, acc[j], xp[j]) : xp[j] + acc[j];
+        xp[0] = xv.x;
+        if (e0 + 1 < m) xp[1] = xv.y;
+        if (e0 + 2 < m) xp[2] = xv.z;
       }
     }
   }
@@ -467,7 +499,13 @@ hipError_t launch_decode_check(const DecodeArgs& a, hipStream_t st) {
 }
 
 hipError_t launch_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t st) {
-  hipLaunchKernelGGL(k_decode_fixed, dim3(blocks), dim3(256), 0, st, a);
+  const dim3 grid(blocks), block(256);
+  switch (a.fixed_bits) {
+    case 2: hipLaunchKernelGGL(k_decode_fixed<2>, grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL(k_decode_fixed<4>, grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL(k_decode_fixed<8>, grid, block, 0, st, a); break;
+    default: hipLaunchKernelGGL(k_decode_fixed<16>, grid, block, 0, st, a); break;
+  }
   return hipGetLastError();
 }
 

@@ -84,7 +84,6 @@ __global__ __launch_bounds__(64 * TW) void k_encode_bucket(EncodeArgs a) {
 
     // ---- read the bucket once, accumulate the scale --------------------------
     float4 v[CPW];
-    double ss = 0.0;
     float mx = 0.f;
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
@@ -92,18 +91,28 @@ __global__ __launch_bounds__(64 * TW) void k_encode_bucket(EncodeArgs a) {
       v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (cstart < m) v[c] = load_quad(gb, cstart + lane * 4, m);
     }
+    // the draws need no data: they are computed while the loads are in flight
+    const uint32_t wstart = (uint32_t)wave * CPW * kChunk;  // bucket position of this wave
+    QuantCtx qc;
+    qc.inv = 0.f; qc.s_f = s_f; qc.s = s; qc.key0 = a.key0; qc.key1 = a.key1;
+    qc.stream_id = a.stream_id; qc.iteration = a.iteration;
+    uint32_t rall[CPW][4];
+    draw_all<CPW, true>(base + wstart, lane, qc, rall);
+    // squares are exact in fp64, so the fused multiply-add rounds like multiply, add
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
       if (a.norm_mode == 0) {
-        ss += (double)v[c].x * (double)v[c].x;
-        ss += (double)v[c].y * (double)v[c].y;
-        ss += (double)v[c].z * (double)v[c].z;
-        ss += (double)v[c].w * (double)v[c].w;
+        s0 = fma((double)v[c].x, (double)v[c].x, s0);
+        s1 = fma((double)v[c].y, (double)v[c].y, s1);
+        s2 = fma((double)v[c].z, (double)v[c].z, s2);
+        s3 = fma((double)v[c].w, (double)v[c].w, s3);
       } else {
         mx = fmaxf(fmaxf(mx, fmaxf(fabsf(v[c].x), fabsf(v[c].y))),
                    fmaxf(fabsf(v[c].z), fabsf(v[c].w)));
       }
     }
+    double ss = (s0 + s1) + (s2 + s3);
     float scale;
     if (a.norm_mode == 0) {
       ss = wave_sum_f64(ss);
@@ -142,10 +151,7 @@ __global__ __launch_bounds__(64 * TW) void k_encode_bucket(EncodeArgs a) {
         const uint32_t cstart = (uint32_t)(wave * CPW + c) * kChunk;
         if (cstart >= m) continue;
         const uint32_t e0 = cstart + lane * 4;
-        const uint64_t q = (base + e0) >> 2;
-        uint32_t r[4];
-        philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.stream_id, a.iteration, a.key0,
-                      a.key1, r);
+        const uint32_t (&r)[4] = rall[c];
         uint32_t z[4];
         z[0] = quantize_one(v[c].x, inv, s_f, s, r[0]);
         z[1] = quantize_one(v[c].y, inv, s_f, s, r[1]);
@@ -202,19 +208,16 @@ __global__ __launch_bounds__(64 * TW) void k_encode_bucket(EncodeArgs a) {
     }
 
     // ---- Elias codes: each wave builds its sub-stream in LDS -----------------
-    QuantCtx qc;
-    qc.inv = inv; qc.s_f = s_f; qc.s = s; qc.key0 = a.key0; qc.key1 = a.key1;
-    qc.stream_id = a.stream_id; qc.iteration = a.iteration;
+    qc.inv = inv;
     WaveOut wo;
     wo.first_pos = 0; wo.last_pos = 0; wo.bits = 0;
     {
-      const uint32_t wstart = (uint32_t)wave * CPW * kChunk;  // bucket position of this wave
       const uint32_t wlen = wstart < m ? min((uint32_t)CPW * kChunk, m - wstart) : 0u;
       const int nchunks = (int)((wlen + kChunk - 1) / kChunk);
       if (CODE == QSGD_CODE_SPARSE)
-        encode_sparse_wave<CPW, false>(v, nchunks, wstart, base + wstart, lane, qc, ring, sub, wo);
+        encode_sparse_wave<CPW, false>(v, rall, nchunks, wstart, lane, qc, ring, sub, wo);
       else
-        encode_dense_wave<CPW>(v, nchunks, wlen, base + wstart, lane, qc, sub, wo);
+        encode_dense_wave<CPW>(v, rall, nchunks, wlen, lane, qc, sub, wo);
     }
     const uint32_t wbits = wo.bits;
 

@@ -66,6 +66,16 @@ __device__ __forceinline__ void draw4(uint64_t gidx, const QuantCtx& q, uint32_t
   }
 }
 
+// Draw words of every chunk a wavefront holds.  They do not depend on the data, so
+// callers compute them while the loads of the values are still in flight.
+template <int CPW, bool ALIGNED>
+__device__ __forceinline__ void draw_all(uint64_t gidx0, int lane, const QuantCtx& q,
+                                         uint32_t (&r)[CPW][4]) {
+#pragma unroll
+  for (int c = 0; c < CPW; ++c)
+    draw4<ALIGNED>(gidx0 + (uint64_t)c * kChunk + (uint64_t)lane * 4u, q, r[c]);
+}
+
 // Stage 2 on `take` (1..64) records starting at ring slot `head`.
 // WIDE: gaps may need more than 21 bits, emit gap and (sign, level) separately.
 template <bool WIDE>
@@ -112,20 +122,20 @@ __device__ __forceinline__ void sparse_flush(const uint32_t* ring, uint32_t head
 //   v[c]      lane's float4 of chunk c (zeros past the end of the data)
 //   nchunks   chunks that hold data (<= CPW)
 //   pos0      bucket position (0-based) of the wavefront's first value
-//   gidx0     global index of the wavefront's first value (ALIGNED: multiple of 4)
+//   rall      draw words of every chunk (draw_all)
 //   ring      kRingWords words of LDS private to this wavefront
 //   sub       zero-initialised LDS words private to this wavefront
-template <int CPW, bool WIDE, bool ALIGNED = true>
-__device__ __forceinline__ void encode_sparse_wave(const float4 (&v)[CPW], int nchunks,
-                                                   uint32_t pos0, uint64_t gidx0, int lane,
+template <int CPW, bool WIDE>
+__device__ __forceinline__ void encode_sparse_wave(const float4 (&v)[CPW],
+                                                   const uint32_t (&rall)[CPW][4], int nchunks,
+                                                   uint32_t pos0, int lane,
                                                    const QuantCtx& q, uint32_t* ring,
                                                    uint32_t* sub, WaveOut& out) {
   uint32_t head = 0, count = 0;
 #pragma unroll
   for (int c = 0; c < CPW; ++c) {
     if (c >= nchunks) break;
-    uint32_t r[4];
-    draw4<ALIGNED>(gidx0 + (uint64_t)c * kChunk + (uint64_t)lane * 4u, q, r);
+    const uint32_t (&r)[4] = rall[c];
     const float ts[4] = {v[c].x * q.inv, v[c].y * q.inv, v[c].z * q.inv, v[c].w * q.inv};
     bool nz[4];
     uint64_t mk[4];
@@ -176,16 +186,16 @@ __device__ __forceinline__ void encode_sparse_wave(const float4 (&v)[CPW], int n
 
 // Code'_s sub-stream (App. A.3): every coordinate sends its sign and Elias(level+1).
 //   len_valid  values that exist in the wavefront's range (the rest is padding)
-template <int CPW, bool ALIGNED = true>
-__device__ __forceinline__ void encode_dense_wave(const float4 (&v)[CPW], int nchunks,
-                                                  uint32_t len_valid, uint64_t gidx0, int lane,
+template <int CPW>
+__device__ __forceinline__ void encode_dense_wave(const float4 (&v)[CPW],
+                                                  const uint32_t (&rall)[CPW][4], int nchunks,
+                                                  uint32_t len_valid, int lane,
                                                   const QuantCtx& q, uint32_t* sub,
                                                   WaveOut& out) {
 #pragma unroll
   for (int c = 0; c < CPW; ++c) {
     if (c >= nchunks) break;
-    uint32_t r[4];
-    draw4<ALIGNED>(gidx0 + (uint64_t)c * kChunk + (uint64_t)lane * 4u, q, r);
+    const uint32_t (&r)[4] = rall[c];
     const float vv[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
     const uint32_t e0 = (uint32_t)c * kChunk + (uint32_t)lane * 4u;
     uint64_t code[4];

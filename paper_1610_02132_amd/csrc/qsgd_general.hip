@@ -176,11 +176,12 @@ __global__ __launch_bounds__(64) void k_gen_encode(GenArgs a) {
     qc.s = a.s; qc.key0 = a.key0; qc.key1 = a.key1;
     qc.stream_id = a.stream_id; qc.iteration = a.iteration;
     const int nchunks = (int)((r.len + kChunk - 1) / kChunk);
+    uint32_t rall[kSegChunks][4];
+    draw_all<kSegChunks, ALIGNED>(r.gidx0, lane, qc, rall);
     if (CODE == QSGD_CODE_SPARSE) {
-      encode_sparse_wave<kSegChunks, true, ALIGNED>(v, nchunks, r.pos0, r.gidx0, lane, qc, ring,
-                                                    sub, wo);
+      encode_sparse_wave<kSegChunks, true>(v, rall, nchunks, r.pos0, lane, qc, ring, sub, wo);
     } else if (CODE == QSGD_CODE_DENSE) {
-      encode_dense_wave<kSegChunks, ALIGNED>(v, nchunks, r.len, r.gidx0, lane, qc, sub, wo);
+      encode_dense_wave<kSegChunks>(v, rall, nchunks, r.len, lane, qc, sub, wo);
     } else {
       // fixed width: fields of 2048 values start on word boundaries in both planes
       const uint32_t B = a.fixed_bits, fmax = (1u << B) - 1u;
@@ -193,8 +194,7 @@ __global__ __launch_bounds__(64) void k_gen_encode(GenArgs a) {
       for (int c = 0; c < kSegChunks; ++c) {
         if (c >= nchunks) break;
         const uint32_t e0 = (uint32_t)c * kChunk + lane * 4;
-        uint32_t rr[4];
-        draw4<ALIGNED>(r.gidx0 + e0, qc, rr);
+        const uint32_t (&rr)[4] = rall[c];
         const float vv[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
         uint32_t z[4], nib = 0;
 #pragma unroll
