@@ -232,14 +232,13 @@ int run_decode(const qsgd_params* p, const void* const* msgs_dev, const size_t* 
     return QSGD_OK;
   }
   // Elias codes: one lane per string.
-  const uint32_t win = (uint32_t)std::min<uint64_t>((g.d + 3) & ~(uint64_t)3, 1024);
+  const uint32_t win = (uint32_t)std::min<uint64_t>((g.d + 3) & ~(uint64_t)3, 256);
   const uint32_t winp = (win + kChunk - 1) / kChunk * kChunk;
   uint32_t gw = 1;  // buckets per wavefront: a power of two, gw * K lanes, gw * winp floats
   while (gw * 2 * K <= 64 && gw * 2 * winp <= 4096) gw *= 2;
   while (gw > 1 && (g.nb + gw - 1) / gw < (uint64_t)cus * 8) gw /= 2;
   a.win = win; a.winp = winp; a.gw = gw; a.rec = std::min(16u, 64u / gw);
-  a.str_words = 3072;
-  const size_t lds = 4 * ((size_t)gw * winp + 64 * a.rec + 256 + a.str_words + 4);
+  const size_t lds = 4 * ((size_t)gw * winp + 64 * a.rec + 192);
   const uint32_t blocks = (uint32_t)((g.nb + gw - 1) / gw);
   ScopedTiming tm("decode_elias", st);
   if (launch_decode_elias(a, blocks, lds, st) != hipSuccess) return QSGD_ERR_HIP;

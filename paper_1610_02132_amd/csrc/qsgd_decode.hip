@@ -58,25 +58,12 @@ __device__ __forceinline__ uint32_t omega_peek(uint32_t w, uint32_t& len) {
   return v;
 }
 
-typedef const __attribute__((address_space(3))) uint32_t* lds_words;
-template <bool STAGED> struct WordPtr;
-template <> struct WordPtr<true> { typedef lds_words type; };         // string copied to LDS
-template <> struct WordPtr<false> { typedef const uint32_t* type; };  // string in global memory
-
 // The 32 stream bits that start at bit `bitpos` of a string (bit j = bit 31-j%32 of
 // word j/32).  Words past the end read as zeros.
-template <bool STAGED>
-__device__ __forceinline__ uint32_t peek_bits(typename WordPtr<STAGED>::type w, uint32_t nwords,
-                                              uint32_t bitpos) {
+__device__ __forceinline__ uint32_t peek_bits(const uint32_t* w, uint32_t nwords, uint32_t bitpos) {
   const uint32_t wi = bitpos >> 5, off = bitpos & 31u;
-  uint32_t hi, lo;
-  if constexpr (STAGED) {  // the LDS copy has slack behind it: no bounds needed
-    hi = w[wi];
-    lo = w[wi + 1];
-  } else {
-    hi = wi < nwords ? w[wi] : 0u;
-    lo = wi + 1 < nwords ? w[wi + 1] : 0u;
-  }
+  const uint32_t hi = wi < nwords ? w[wi] : 0u;
+  const uint32_t lo = wi + 1 < nwords ? w[wi + 1] : 0u;
   return (uint32_t)((((uint64_t)hi << 32) | lo) >> (32u - off));
 }
 
@@ -216,24 +203,21 @@ __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
 }
 
 // ---- Elias codes: one lane per string, gw buckets x K messages per wavefront -------
-// Per wavefront: (1) the strings of its gw buckets are contiguous in each message,
-// so they are copied to LDS with coalesced loads (when they fit; else lanes read
-// them from global memory); (2) per window of `win` bucket positions the x values
-// are fetched into registers first, so that their latency hides behind the
-// parsing; (3) every lane parses ahead into its own small ring of records, and
-// records are applied to the LDS accumulator in message order, but only up to
+// Per wavefront: (1) per window of `win` bucket positions the x values are fetched
+// into registers first, so that their latency hides behind the parsing; (2) every
+// lane parses ahead into its own small ring of records, reading its string straight
+// from global memory (L1/L2 resident; staging the strings in LDS was measured
+// slower: the LDS it takes costs more occupancy than the loads cost latency);
+// (3) records are applied to the LDS accumulator in message order, but only up to
 // the position every string has been parsed to; (4) registers and accumulator
-// are combined and stored.
-constexpr int kMaxQuads = 16;   // float4 per lane per window: gw * winp <= 4096 floats
-constexpr uint32_t kStrSlack = 4;  // readable words behind the staged strings
+// are combined and stored.  Little LDS per wavefront (small windows) matters more
+// than long windows: the kernel lives on occupancy.
 
 // CODE: sparse or dense Elias code.  LG: groups a level's code word may have.
-template <int CODE, int LG, bool STAGED>
+template <int CODE, int LG, int NQ>
 __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* acc, uint32_t* queue,
                                                   uint32_t* counts, uint32_t* heads,
-                                                  float* scales, const uint32_t* starts,
-                                                  uint32_t* strs, uint32_t total, uint32_t b0,
-                                                  uint32_t gcount) {
+                                                  float* scales, uint32_t b0, uint32_t gcount) {
   constexpr bool kSparse = CODE == QSGD_CODE_SPARSE;
   // a whole record in one 32-bit peek: gap <= 21 bits, sign, level <= 7 bits
   constexpr bool kNarrow = !kSparse || LG <= 2;
@@ -250,18 +234,16 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   uint32_t bitpos = 32;   // next unread bit (after the scale)
   uint32_t nwords = 0;
   uint32_t pend_pos = 0, pend_lev = 0, pend_neg = 0;  // pend_pos is 1-based
-  typename WordPtr<STAGED>::type str = nullptr;
+  const uint32_t* str = nullptr;
   bool open = false;
   float my_scale = 0.f;
   if (g < gcount) {
     m = (uint32_t)min((uint64_t)a.d, a.n - (uint64_t)b * a.d);
     const uint32_t* msg = a.msgs[k];
     const uint32_t o0 = msg[H_WORDS + b], o1 = msg[H_WORDS + b + 1];
-    const uint32_t kr0 = msg[H_WORDS + b0];  // start of message k's range
-    if (o0 < o1 && kr0 <= o0 && pay + o1 <= a.msg_words[k] && (!STAGED || o1 - kr0 <= total)) {
+    if (o0 < o1 && pay + o1 <= a.msg_words[k]) {
       nwords = o1 - o0;
-      if constexpr (STAGED) str = (lds_words)(strs + starts[k] + (o0 - kr0));
-      else str = msg + pay + o0;
+      str = msg + pay + o0;
       my_scale = __uint_as_float(str[0]) / (float)s;
       open = true;
       if (kSparse) {
@@ -281,14 +263,14 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     if (kSparse) {
       if (bitpos >= endbit) { have = false; return; }
       uint32_t gl, ll, gap, lev;
-      const uint32_t w = peek_bits<STAGED>(str, nwords, bitpos);
+      const uint32_t w = peek_bits(str, nwords, bitpos);
       gap = omega_peek<3>(w, gl);
       if (kNarrow) {
         const uint32_t x = w << gl;
         pend_neg = x >> 31;
         lev = omega_peek<LG>(x << 1, ll);
       } else {
-        const uint32_t x = peek_bits<STAGED>(str, nwords, bitpos + gl);
+        const uint32_t x = peek_bits(str, nwords, bitpos + gl);
         pend_neg = x >> 31;
         lev = omega_peek<LG>(x << 1, ll);
       }
@@ -302,7 +284,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     } else {
       if (pend_pos >= m) { have = false; return; }
       uint32_t ll;
-      const uint32_t w = peek_bits<STAGED>(str, nwords, bitpos);
+      const uint32_t w = peek_bits(str, nwords, bitpos);
       const uint32_t lev1 = omega_peek<LG>(w << 1, ll);
       bitpos += 1u + ll;
       pend_neg = w >> 31;
@@ -319,16 +301,16 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   for (uint32_t j = lane; j < gw * winp; j += 64) acc[j] = 0.f;
   __syncthreads();
 
-  const uint32_t nq = gw * winp / kChunk;  // float4 per lane per window (<= kMaxQuads)
+  const uint32_t nq = gw * winp / kChunk;  // float4 per lane per window (<= NQ)
   uint32_t qhead = 0, qcnt = 0;            // this lane's ring of queued records
   const uint32_t g2 = lane / rec, r = lane - g2 * rec;  // apply role: bucket g2, ring slot r
   for (uint32_t ws = 0; ws < a.d; ws += win) {
     const uint32_t wend = ws + win;  // positions (1-based) up to wend fall in this window
     // ---- fetch this window of x into registers (latency hides behind the parsing) ----
-    float4 xr[kMaxQuads];
+    float4 xr[NQ];
     uint32_t gg = 0, i0 = 0;  // bucket and offset of quad qi (wave-uniform)
 #pragma unroll
-    for (int qi = 0; qi < kMaxQuads; ++qi) {
+    for (int qi = 0; qi < NQ; ++qi) {
       xr[qi] = make_float4(0.f, 0.f, 0.f, 0.f);
       if ((uint32_t)qi < nq) {
         const uint32_t i = i0 + (uint32_t)lane * 4u;
@@ -394,7 +376,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     // ---- combine the accumulator with x and store ------------------------------------
     gg = 0; i0 = 0;
 #pragma unroll
-    for (int qi = 0; qi < kMaxQuads; ++qi) {
+    for (int qi = 0; qi < NQ; ++qi) {
       if ((uint32_t)qi < nq) {
         const uint32_t i = i0 + (uint32_t)lane * 4u;
         if (gg < gcount) {
@@ -430,67 +412,20 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   }
 }
 
-template <int CODE, int LG>
+template <int CODE, int LG, int NQ>
 __global__ __launch_bounds__(64) void k_decode_elias(DecodeArgs a) {
   if (*a.status != 0) return;
   extern __shared__ uint32_t smem[];
-  // LDS: [acc: gw*winp floats][rings: 64*rec][counts 64][heads 64][scales 64][starts 64][strings]
-  const uint32_t K = a.K, gw = a.gw, winp = a.winp, rec = a.rec;
+  // LDS: [acc: gw*winp floats][rings: 64*rec][counts 64][heads 64][scales 64]
+  const uint32_t gw = a.gw, winp = a.winp, rec = a.rec;
   float* const acc = reinterpret_cast<float*>(smem);
   uint32_t* const queue = smem + gw * winp;
   uint32_t* const counts = queue + 64u * rec;
   uint32_t* const heads = counts + 64;
   float* const scales = reinterpret_cast<float*>(counts + 128);
-  uint32_t* const starts = counts + 192;
-  uint32_t* const strs = counts + 256;
-
-  const int lane = threadIdx.x;
   const uint32_t b0 = blockIdx.x * gw;
   const uint32_t gcount = min(gw, a.nb - b0);  // buckets this wavefront really has
-  const uint64_t pay = (uint64_t)H_WORDS + a.table_words;
-
-  // ---- stage the strings: message k's part is words [r0, r1) of its payload --------
-  uint32_t r0 = 0, rlen = 0;
-  bool range_ok = true;
-  if ((uint32_t)lane < K) {
-    const uint32_t* msg = a.msgs[lane];
-    r0 = msg[H_WORDS + b0];
-    const uint32_t r1 = msg[H_WORDS + b0 + gcount];
-    range_ok = r0 <= r1 && pay + r1 <= a.msg_words[lane];
-    rlen = range_ok ? r1 - r0 : 0u;
-  }
-  const uint32_t incl = wave_incl_scan_u32(rlen, lane);
-  const uint32_t total = lane_bcast(incl, 63);
-  const bool staged = total <= a.str_words;
-  if ((uint32_t)lane < K) starts[lane] = incl - rlen;
-  if (!range_ok) flag_corrupt(a.status);
-  if (staged) {
-    for (uint32_t kk = 0; kk < K; ++kk) {
-      const uint32_t len = lane_bcast(rlen, (int)kk);
-      const uint32_t l0 = lane_bcast(incl - rlen, (int)kk);
-      const uint32_t* src = a.msgs[kk] + pay + lane_bcast(r0, (int)kk);
-      for (uint32_t w = lane; w < len; w += 256) {
-        const uint32_t w1 = w + 64, w2 = w + 128, w3 = w + 192;
-        const uint32_t x0 = src[w];
-        const uint32_t x1 = w1 < len ? src[w1] : 0u;
-        const uint32_t x2 = w2 < len ? src[w2] : 0u;
-        const uint32_t x3 = w3 < len ? src[w3] : 0u;
-        strs[l0 + w] = x0;
-        if (w1 < len) strs[l0 + w1] = x1;
-        if (w2 < len) strs[l0 + w2] = x2;
-        if (w3 < len) strs[l0 + w3] = x3;
-      }
-    }
-    if ((uint32_t)lane < kStrSlack) strs[total + lane] = 0;
-  }
-  __syncthreads();
-
-  if (staged)
-    decode_elias_body<CODE, LG, true>(a, acc, queue, counts, heads, scales, starts, strs, total,
-                                      b0, gcount);
-  else
-    decode_elias_body<CODE, LG, false>(a, acc, queue, counts, heads, scales, starts, strs, total,
-                                       b0, gcount);
+  decode_elias_body<CODE, LG, NQ>(a, acc, queue, counts, heads, scales, b0, gcount);
 }
 
 hipError_t launch_decode_check(const DecodeArgs& a, hipStream_t st) {
@@ -509,17 +444,26 @@ hipError_t launch_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t
   return hipGetLastError();
 }
 
+template <int CODE, int NQ>
+static hipError_t launch_elias_nq(const DecodeArgs& a, int lg, uint32_t blocks, size_t lds,
+                                  hipStream_t st) {
+  const dim3 grid(blocks), block(64);
+  switch (lg) {
+    case 1: hipLaunchKernelGGL((k_decode_elias<CODE, 1, NQ>), grid, block, lds, st, a); break;
+    case 2: hipLaunchKernelGGL((k_decode_elias<CODE, 2, NQ>), grid, block, lds, st, a); break;
+    case 3: hipLaunchKernelGGL((k_decode_elias<CODE, 3, NQ>), grid, block, lds, st, a); break;
+    default: hipLaunchKernelGGL((k_decode_elias<CODE, 4, NQ>), grid, block, lds, st, a); break;
+  }
+  return hipGetLastError();
+}
+
 template <int CODE>
 static hipError_t launch_elias_code(const DecodeArgs& a, int lg, uint32_t blocks, size_t lds,
                                     hipStream_t st) {
-  const dim3 grid(blocks), block(64);
-  switch (lg) {
-    case 1: hipLaunchKernelGGL((k_decode_elias<CODE, 1>), grid, block, lds, st, a); break;
-    case 2: hipLaunchKernelGGL((k_decode_elias<CODE, 2>), grid, block, lds, st, a); break;
-    case 3: hipLaunchKernelGGL((k_decode_elias<CODE, 3>), grid, block, lds, st, a); break;
-    default: hipLaunchKernelGGL((k_decode_elias<CODE, 4>), grid, block, lds, st, a); break;
-  }
-  return hipGetLastError();
+  const uint32_t nq = a.gw * a.winp / kChunk;  // float4 of x per lane per window
+  if (nq <= 4) return launch_elias_nq<CODE, 4>(a, lg, blocks, lds, st);
+  if (nq <= 8) return launch_elias_nq<CODE, 8>(a, lg, blocks, lds, st);
+  return launch_elias_nq<CODE, 16>(a, lg, blocks, lds, st);
 }
 
 // Groups in the longest level code word: Elias(s) (sparse) or Elias(s + 1) (dense).

@@ -23,6 +23,9 @@ enum HeaderWord : int {
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2,
                                               uint32_t c3, uint32_t k0, uint32_t k1,
                                               uint32_t out[4]) {
+  // Keep the key schedule in two scalar registers per call (scalar adds per round)
+  // instead of letting twenty precomputed round keys occupy scalar registers.
+  asm volatile("" : "+s"(k0), "+s"(k1));
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
     const uint64_t p0 = (uint64_t)0xD2511F53u * c0;

@@ -67,7 +67,6 @@ struct DecodeArgs {
   uint32_t gw;           // buckets per wavefront
   uint32_t win;          // window (positions per bucket per pass), multiple of 4
   uint32_t winp;         // accumulator stride per bucket: win rounded up to 256
-  uint32_t str_words;    // LDS words available for staged strings
   uint32_t rec;          // record slots per string per round
   // fixed width
   uint32_t fixed_bits;
