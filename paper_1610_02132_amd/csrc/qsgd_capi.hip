@@ -235,7 +235,7 @@ int run_decode(const qsgd_params* p, const void* const* msgs_dev, const size_t* 
   const uint32_t win = (uint32_t)std::min<uint64_t>((g.d + 3) & ~(uint64_t)3, 256);
   const uint32_t winp = (win + kChunk - 1) / kChunk * kChunk;
   uint32_t gw = 1;  // buckets per wavefront: a power of two, gw * K lanes, gw * winp floats
-  while (gw * 2 * K <= 64 && gw * 2 * winp <= 4096) gw *= 2;
+  while (gw * 2 * K <= 64 && gw * 2 <= 16) gw *= 2;
   while (gw > 1 && (g.nb + gw - 1) / gw < (uint64_t)cus * 8) gw /= 2;
   a.win = win; a.winp = winp; a.gw = gw; a.rec = std::min(16u, 64u / gw);
   const size_t lds = 4 * ((size_t)gw * winp + 64 * a.rec + 192);

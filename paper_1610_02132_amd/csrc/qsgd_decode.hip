@@ -221,7 +221,8 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   constexpr bool kSparse = CODE == QSGD_CODE_SPARSE;
   // a whole record in one 32-bit peek: gap <= 21 bits, sign, level <= 7 bits
   constexpr bool kNarrow = !kSparse || LG <= 2;
-  const uint32_t K = a.K, gw = a.gw, win = a.win, winp = a.winp, rec = a.rec, s = a.s;
+  const uint32_t K = a.K, gw = a.gw, win = a.win, rec = a.rec, s = a.s;
+  constexpr uint32_t winp = kChunk;  // accumulator stride per bucket
   const int lane = threadIdx.x;
   const uint64_t pay = (uint64_t)H_WORDS + a.table_words;
 
@@ -301,49 +302,50 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   for (uint32_t j = lane; j < gw * winp; j += 64) acc[j] = 0.f;
   __syncthreads();
 
-  const uint32_t nq = gw * winp / kChunk;  // float4 per lane per window (<= NQ)
+  // A window is at most 256 positions (winp = 256): quad q of the x registers is
+  // bucket q of this wavefront, lane l holds positions 4l..4l+3 of the window.
   uint32_t qhead = 0, qcnt = 0;            // this lane's ring of queued records
   const uint32_t g2 = lane / rec, r = lane - g2 * rec;  // apply role: bucket g2, ring slot r
+  const uint32_t i = (uint32_t)lane * 4u;
   for (uint32_t ws = 0; ws < a.d; ws += win) {
     const uint32_t wend = ws + win;  // positions (1-based) up to wend fall in this window
     // ---- fetch this window of x into registers (latency hides behind the parsing) ----
     float4 xr[NQ];
-    uint32_t gg = 0, i0 = 0;  // bucket and offset of quad qi (wave-uniform)
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
       xr[qi] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if ((uint32_t)qi < nq) {
-        const uint32_t i = i0 + (uint32_t)lane * 4u;
-        if (gg < gcount) {
-          const uint64_t base = (uint64_t)(b0 + gg) * a.d;
-          const uint32_t mb = (uint32_t)min((uint64_t)a.d, a.n - base);
-          const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
-          const float* xp = a.x + base + ws + i;
-          if (i + 3 < cntw) {
-            xr[qi] = *reinterpret_cast<const float4*>(xp);
-          } else {
-            if (i + 0 < cntw) xr[qi].x = xp[0];
-            if (i + 1 < cntw) xr[qi].y = xp[1];
-            if (i + 2 < cntw) xr[qi].z = xp[2];
-          }
+      if ((uint32_t)qi < gcount) {
+        const uint64_t base = (uint64_t)(b0 + qi) * a.d;
+        const uint32_t mb = (uint32_t)min((uint64_t)a.d, a.n - base);
+        const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
+        const float* xp = a.x + base + ws + i;
+        if (i + 3 < cntw) {
+          xr[qi] = *reinterpret_cast<const float4*>(xp);
+        } else {
+          if (i + 0 < cntw) xr[qi].x = xp[0];
+          if (i + 1 < cntw) xr[qi].y = xp[1];
+          if (i + 2 < cntw) xr[qi].z = xp[2];
         }
-        i0 += kChunk;
-        if (i0 >= winp) { i0 = 0; ++gg; }
       }
     }
     // ---- rounds: parse ahead into the rings, apply what is due --------------------------
     // A position may only be applied once EVERY string has been parsed past it,
     // or an element could receive message 5's term before message 2's.  `limit`
     // is the smallest position still pending in any string, minus 1, capped at
-    // the window end; queued records past it wait in the ring.
+    // the window end; queued records past it wait in the ring.  Parsing is lazy:
+    // nobody parses while every string is already past the window end, and when
+    // some string is not, all of them fill their rings (fewer, fuller passes of
+    // the divergent parse loop).
     for (;;) {
-      while (have && qcnt < rec) {
-        if (pend_lev) {
-          queue[lane * rec + ((qhead + qcnt) & (rec - 1))] =
-              (pend_pos - 1u) | (pend_neg << 13) | (pend_lev << 14);
-          ++qcnt;
+      if (__ballot(have && pend_pos <= wend) != 0) {
+        while (have && qcnt < rec) {
+          if (pend_lev) {
+            queue[lane * rec + ((qhead + qcnt) & (rec - 1))] =
+                (pend_pos - 1u) | (pend_neg << 13) | (pend_lev << 14);
+            ++qcnt;
+          }
+          advance();
         }
-        advance();
       }
       uint32_t limit = have ? pend_pos - 1u : 0xFFFFFFFFu;
 #pragma unroll
@@ -374,38 +376,32 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       if (limit == wend) break;   // uniform: every string is parsed past this window
     }
     // ---- combine the accumulator with x and store ------------------------------------
-    gg = 0; i0 = 0;
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
-      if ((uint32_t)qi < nq) {
-        const uint32_t i = i0 + (uint32_t)lane * 4u;
-        if (gg < gcount) {
-          const uint64_t base = (uint64_t)(b0 + gg) * a.d;
-          const uint32_t mb = (uint32_t)min((uint64_t)a.d, a.n - base);
-          const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
-          float* xp = a.x + base + ws + i;
-          float* ap = acc + gg * winp + i;
-          if (i < cntw) {
-            const float4 av = *reinterpret_cast<float4*>(ap);
-            *reinterpret_cast<float4*>(ap) = make_float4(0.f, 0.f, 0.f, 0.f);
-            float4 xv = xr[qi];
-            if (a.step) {
-              xv.x = fmaf(-a.c, av.x, xv.x); xv.y = fmaf(-a.c, av.y, xv.y);
-              xv.z = fmaf(-a.c, av.z, xv.z); xv.w = fmaf(-a.c, av.w, xv.w);
-            } else {
-              xv.x += av.x; xv.y += av.y; xv.z += av.z; xv.w += av.w;
-            }
-            if (i + 3 < cntw) {
-              *reinterpret_cast<float4*>(xp) = xv;
-            } else {
-              xp[0] = xv.x;
-              if (i + 1 < cntw) xp[1] = xv.y;
-              if (i + 2 < cntw) xp[2] = xv.z;
-            }
+      if ((uint32_t)qi < gcount) {
+        const uint64_t base = (uint64_t)(b0 + qi) * a.d;
+        const uint32_t mb = (uint32_t)min((uint64_t)a.d, a.n - base);
+        const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
+        float* xp = a.x + base + ws + i;
+        float* ap = acc + qi * winp + i;
+        if (i < cntw) {
+          const float4 av = *reinterpret_cast<float4*>(ap);
+          *reinterpret_cast<float4*>(ap) = make_float4(0.f, 0.f, 0.f, 0.f);
+          float4 xv = xr[qi];
+          if (a.step) {
+            xv.x = fmaf(-a.c, av.x, xv.x); xv.y = fmaf(-a.c, av.y, xv.y);
+            xv.z = fmaf(-a.c, av.z, xv.z); xv.w = fmaf(-a.c, av.w, xv.w);
+          } else {
+            xv.x += av.x; xv.y += av.y; xv.z += av.z; xv.w += av.w;
+          }
+          if (i + 3 < cntw) {
+            *reinterpret_cast<float4*>(xp) = xv;
+          } else {
+            xp[0] = xv.x;
+            if (i + 1 < cntw) xp[1] = xv.y;
+            if (i + 2 < cntw) xp[2] = xv.z;
           }
         }
-        i0 += kChunk;
-        if (i0 >= winp) { i0 = 0; ++gg; }
       }
     }
     __syncthreads();
@@ -460,7 +456,7 @@ static hipError_t launch_elias_nq(const DecodeArgs& a, int lg, uint32_t blocks, 
 template <int CODE>
 static hipError_t launch_elias_code(const DecodeArgs& a, int lg, uint32_t blocks, size_t lds,
                                     hipStream_t st) {
-  const uint32_t nq = a.gw * a.winp / kChunk;  // float4 of x per lane per window
+  const uint32_t nq = a.gw;  // float4 of x per lane per window: one per bucket
   if (nq <= 4) return launch_elias_nq<CODE, 4>(a, lg, blocks, lds, st);
   if (nq <= 8) return launch_elias_nq<CODE, 8>(a, lg, blocks, lds, st);
   return launch_elias_nq<CODE, 16>(a, lg, blocks, lds, st);
