@@ -52,8 +52,8 @@ __device__ __forceinline__ uint32_t quantize_one(float v, float inv, float s_f, 
   const float fl = floorf(t);
   const float p = t - fl;
   const float u = (float)(word >> 8) * (1.0f / 16777216.0f);
-  const uint32_t z = (uint32_t)fl + ((u < p) ? 1u : 0u);
-  return (fl >= s_f) ? s : z;
+  // t >= s (a = 1 up to rounding) must give the top level: l + [u < p] >= s then
+  return min((uint32_t)fl + ((u < p) ? 1u : 0u), s);
 }
 
 // ---- recursive Elias code (App. A.2): a '0' at the end, binary groups in front ---
@@ -106,25 +106,56 @@ __device__ __forceinline__ void global_emit(uint32_t* words, uint64_t bitoff, ui
 }
 
 // ---- wavefront helpers ----------------------------------------------------------
-__device__ __forceinline__ double wave_sum_f64(double v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-  return v;
+// Cross-lane data movement uses DPP modifiers (row shifts inside rows of 16 lanes,
+// then broadcasts of lane 15 / lane 31 into the following rows): one VALU
+// instruction per step and no LDS traffic.  Lanes without a source read 0, which
+// is the identity of every combination used here (sums, max of magnitudes).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_fetch(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+constexpr int kDppShr1 = 0x111, kDppShr2 = 0x112, kDppShr4 = 0x114, kDppShr8 = 0x118;
+constexpr int kDppBcast15 = 0x142, kDppBcast31 = 0x143;
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_fetch_f64(double v) {
+  const uint32_t lo = dpp_fetch<CTRL, ROW_MASK>((uint32_t)__double2loint(v));
+  const uint32_t hi = dpp_fetch<CTRL, ROW_MASK>((uint32_t)__double2hiint(v));
+  return __hiloint2double((int)hi, (int)lo);
 }
 
+// Sum over the 64 lanes, the same value returned to every lane.
+__device__ __forceinline__ double wave_sum_f64(double v) {
+  v += dpp_fetch_f64<kDppShr1, 0xf>(v);
+  v += dpp_fetch_f64<kDppShr2, 0xf>(v);
+  v += dpp_fetch_f64<kDppShr4, 0xf>(v);
+  v += dpp_fetch_f64<kDppShr8, 0xf>(v);
+  v += dpp_fetch_f64<kDppBcast15, 0xa>(v);
+  v += dpp_fetch_f64<kDppBcast31, 0xc>(v);
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+  return __hiloint2double(hi, lo);
+}
+
+// Max over the 64 lanes of non-negative values.
 __device__ __forceinline__ float wave_max_f32(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-  return v;
+  v = fmaxf(v, __uint_as_float(dpp_fetch<kDppShr1, 0xf>(__float_as_uint(v))));
+  v = fmaxf(v, __uint_as_float(dpp_fetch<kDppShr2, 0xf>(__float_as_uint(v))));
+  v = fmaxf(v, __uint_as_float(dpp_fetch<kDppShr4, 0xf>(__float_as_uint(v))));
+  v = fmaxf(v, __uint_as_float(dpp_fetch<kDppShr8, 0xf>(__float_as_uint(v))));
+  v = fmaxf(v, __uint_as_float(dpp_fetch<kDppBcast15, 0xa>(__float_as_uint(v))));
+  v = fmaxf(v, __uint_as_float(dpp_fetch<kDppBcast31, 0xc>(__float_as_uint(v))));
+  return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(v), 63));
 }
 
 // Inclusive prefix sum over the 64 lanes.
-__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int lane) {
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const uint32_t t = __shfl_up(v, o, kWave);
-    if (lane >= o) v += t;
-  }
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int /*lane*/) {
+  v += dpp_fetch<kDppShr1, 0xf>(v);
+  v += dpp_fetch<kDppShr2, 0xf>(v);
+  v += dpp_fetch<kDppShr4, 0xf>(v);
+  v += dpp_fetch<kDppShr8, 0xf>(v);
+  v += dpp_fetch<kDppBcast15, 0xa>(v);
+  v += dpp_fetch<kDppBcast31, 0xc>(v);
   return v;
 }
 
