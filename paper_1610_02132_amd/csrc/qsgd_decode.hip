@@ -347,9 +347,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
           advance();
         }
       }
-      uint32_t limit = have ? pend_pos - 1u : 0xFFFFFFFFu;
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) limit = min(limit, (uint32_t)__shfl_xor((int)limit, o, kWave));
+      uint32_t limit = wave_min_u32(have ? pend_pos - 1u : 0xFFFFFFFFu);
       limit = min(limit, wend);   // 0-based positions below `limit` are due
       counts[lane] = qcnt;
       heads[lane] = qhead;

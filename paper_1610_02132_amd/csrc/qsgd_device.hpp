@@ -114,6 +114,11 @@ template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ uint32_t dpp_fetch(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
 }
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_fetch_or(uint32_t other, uint32_t v) {  // `other` where no source
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)other, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+constexpr int kDppShl1 = 0x101, kDppShl2 = 0x102, kDppShl4 = 0x104;  // lane l reads lane l+k of its row
 constexpr int kDppShr1 = 0x111, kDppShr2 = 0x112, kDppShr4 = 0x114, kDppShr8 = 0x118;
 constexpr int kDppBcast15 = 0x142, kDppBcast31 = 0x143;
 
@@ -146,6 +151,17 @@ __device__ __forceinline__ float wave_max_f32(float v) {
   v = fmaxf(v, __uint_as_float(dpp_fetch<kDppBcast15, 0xa>(__float_as_uint(v))));
   v = fmaxf(v, __uint_as_float(dpp_fetch<kDppBcast31, 0xc>(__float_as_uint(v))));
   return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(v), 63));
+}
+
+// Min over the 64 lanes, returned to every lane.
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+  v = min(v, dpp_fetch_or<kDppShr1, 0xf>(0xFFFFFFFFu, v));
+  v = min(v, dpp_fetch_or<kDppShr2, 0xf>(0xFFFFFFFFu, v));
+  v = min(v, dpp_fetch_or<kDppShr4, 0xf>(0xFFFFFFFFu, v));
+  v = min(v, dpp_fetch_or<kDppShr8, 0xf>(0xFFFFFFFFu, v));
+  v = min(v, dpp_fetch_or<kDppBcast15, 0xa>(0xFFFFFFFFu, v));
+  v = min(v, dpp_fetch_or<kDppBcast31, 0xc>(0xFFFFFFFFu, v));
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
 // Inclusive prefix sum over the 64 lanes.

@@ -173,21 +173,21 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
           if (wi + 1 < lw) lplane[wi + 1] = z[2] | (z[3] << 16);
         } else if (B == 4) {
           uint32_t h = z[0] | (z[1] << 4) | (z[2] << 8) | (z[3] << 12);
-          h |= __shfl_down(h, 1, kWave) << 16;
+          h |= dpp_fetch<kDppShl1, 0xf>(h) << 16;
           const uint32_t wi = e0 >> 3;
           if ((lane & 1) == 0 && wi < lw) lplane[wi] = h;
         } else {  // B == 2
           uint32_t h = z[0] | (z[1] << 2) | (z[2] << 4) | (z[3] << 6);
-          h |= __shfl_down(h, 1, kWave) << 8;
-          h |= __shfl_down(h, 2, kWave) << 16;
+          h |= dpp_fetch<kDppShl1, 0xf>(h) << 8;
+          h |= dpp_fetch<kDppShl2, 0xf>(h) << 16;
           const uint32_t wi = e0 >> 4;
           if ((lane & 3) == 0 && wi < lw) lplane[wi] = h;
         }
         // sign plane: element i at bit i%32 of word i/32
         uint32_t sg = nib;
-        sg |= __shfl_down(sg, 1, kWave) << 4;
-        sg |= __shfl_down(sg, 2, kWave) << 8;
-        sg |= __shfl_down(sg, 4, kWave) << 16;
+        sg |= dpp_fetch<kDppShl1, 0xf>(sg) << 4;
+        sg |= dpp_fetch<kDppShl2, 0xf>(sg) << 8;
+        sg |= dpp_fetch<kDppShl4, 0xf>(sg) << 16;
         const uint32_t si = e0 >> 5;
         if ((lane & 7) == 0 && si < sw) splane[si] = sg;
       }

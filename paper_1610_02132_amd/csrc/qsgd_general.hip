@@ -210,18 +210,18 @@ __global__ __launch_bounds__(64) void k_gen_encode(GenArgs a) {
           if ((e0 >> 1) + 1 < lwn) lplane[(e0 >> 1) + 1] = z[2] | (z[3] << 16);
         } else if (B == 4) {
           uint32_t h = z[0] | (z[1] << 4) | (z[2] << 8) | (z[3] << 12);
-          h |= __shfl_down(h, 1, kWave) << 16;
+          h |= dpp_fetch<kDppShl1, 0xf>(h) << 16;
           if ((lane & 1) == 0 && (e0 >> 3) < lwn) lplane[e0 >> 3] = h;
         } else {
           uint32_t h = z[0] | (z[1] << 2) | (z[2] << 4) | (z[3] << 6);
-          h |= __shfl_down(h, 1, kWave) << 8;
-          h |= __shfl_down(h, 2, kWave) << 16;
+          h |= dpp_fetch<kDppShl1, 0xf>(h) << 8;
+          h |= dpp_fetch<kDppShl2, 0xf>(h) << 16;
           if ((lane & 3) == 0 && (e0 >> 4) < lwn) lplane[e0 >> 4] = h;
         }
         uint32_t sg = nib;
-        sg |= __shfl_down(sg, 1, kWave) << 4;
-        sg |= __shfl_down(sg, 2, kWave) << 8;
-        sg |= __shfl_down(sg, 4, kWave) << 16;
+        sg |= dpp_fetch<kDppShl1, 0xf>(sg) << 4;
+        sg |= dpp_fetch<kDppShl2, 0xf>(sg) << 8;
+        sg |= dpp_fetch<kDppShl4, 0xf>(sg) << 16;
         if ((lane & 7) == 0 && (e0 >> 5) < swn) splane[e0 >> 5] = sg;
       }
     }
