@@ -372,6 +372,20 @@ int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t 
   a.fixed_bits = g.fixed_bits;
   a.fixed_words_full = (uint32_t)g.max_words(g.d);
   a.fixed_payload_words = g.code == QSGD_CODE_FIXED ? g.max_payload_words() : 0;
+  if (g.code == QSGD_CODE_FIXED && g.d <= 1024) {
+    // small buckets: several ride in one wavefront
+    const int lpb = g.d <= 256 ? 16 : g.d <= 512 ? 32 : 64;
+    const int cp = (int)((g.d + lpb * 4 - 1) / (lpb * 4));
+    const uint32_t per_pass = 64u / lpb;
+    const uint32_t groups = (uint32_t)((g.nb + per_pass - 1) / per_pass);
+    const uint32_t want = std::min<uint32_t>(kMaxTeams, (uint32_t)device_cus() * 32u);
+    const uint32_t t = std::max(1u, std::min(groups, want));
+    a.bper = (groups + t - 1) / t;
+    const uint32_t teams = (groups + a.bper - 1) / a.bper;
+    ScopedTiming tm("encode_bucket", st);
+    if (launch_encode_fixed_small(a, lpb, cp, teams, st) != hipSuccess) return QSGD_ERR_HIP;
+    return QSGD_OK;
+  }
   {
     ScopedTiming tm("encode_bucket", st);
     if (launch_encode_bucket(a, g.code, pl.tw, pl.cpw, pl.teams, pl.lds, st) != hipSuccess)

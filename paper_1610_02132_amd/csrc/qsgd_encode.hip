@@ -279,6 +279,169 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
   if (CODE != QSGD_CODE_FIXED && tid == 0) a.totals[blockIdx.x] = run;
 }
 
+// Fixed width, buckets of at most 1024 values: LPB lanes per bucket (64 / LPB buckets
+// per wavefront at once), CP float4 per lane, B-bit fields.  Offsets are closed
+// form, so the wavefront reads its buckets once and writes their strings in place;
+// the per-bucket work (scale reduction, square root, divide) is shared by the
+// buckets that ride in one wavefront.
+template <int LPB, int CP, int B>
+__global__ __launch_bounds__(64) void k_encode_fixed_small(EncodeArgs a) {
+  constexpr int NB = 64 / LPB;             // buckets per wavefront pass
+  constexpr uint32_t kStep = LPB * 4;      // values one pass of the bucket's lanes covers
+  constexpr uint32_t fmax = (1u << B) - 1u;
+  const int lane = threadIdx.x;
+  const uint32_t sb = lane / LPB, l = lane % LPB;
+  const int last_lane = (int)(sb * LPB + LPB - 1);
+
+  if (blockIdx.x == 0 && lane == 0) {
+    uint32_t* h = a.header;
+    h[H_MAGIC] = kMagic; h[H_VERSION] = 1; h[H_CODE] = QSGD_CODE_FIXED; h[H_NORM] = a.norm_mode;
+    h[H_S] = a.s; h[H_STREAM] = a.stream_id;
+    h[H_D_LO] = (uint32_t)a.d; h[H_D_HI] = 0;
+    h[H_N_LO] = (uint32_t)a.n; h[H_N_HI] = (uint32_t)(a.n >> 32);
+    h[H_NB_LO] = a.nb; h[H_NB_HI] = 0;
+    h[H_PW_LO] = (uint32_t)a.fixed_payload_words;
+    h[H_PW_HI] = (uint32_t)(a.fixed_payload_words >> 32);
+    h[H_STATUS] = 0; h[H_ITER] = a.iteration;
+  }
+  const uint32_t s = a.s;
+  const float s_f = (float)s;
+  QuantCtx qc;
+  qc.inv = 0.f; qc.s_f = s_f; qc.s = s; qc.key0 = a.key0; qc.key1 = a.key1;
+  qc.stream_id = a.stream_id; qc.iteration = a.iteration;
+
+  const uint32_t g_begin = blockIdx.x * a.bper;               // bucket groups of this team
+  const uint32_t g_end = min(g_begin + a.bper, (a.nb + NB - 1) / NB);
+  for (uint32_t grp = g_begin; grp < g_end; ++grp) {
+    const uint32_t b = grp * NB + sb;
+    const bool live = b < a.nb;
+    const uint64_t base = (uint64_t)b * a.d;
+    const uint32_t m = live ? (uint32_t)min((uint64_t)a.d, a.n - base) : 0u;
+    const float* __restrict__ gb = a.g + base;
+    // every lane's CP quads lie inside its bucket: no per-element bounds needed
+    const bool all_full = __ballot(m == (uint32_t)CP * kStep) == ~0ull;
+
+    float4 v[CP];
+    uint32_t r[CP][4];
+#pragma unroll
+    for (int c = 0; c < CP; ++c) {
+      const uint32_t e0 = (uint32_t)c * kStep + l * 4;
+      if (all_full) {
+        v[c] = *reinterpret_cast<const float4*>(gb + e0);
+      } else {
+        v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (e0 + 3 < m) {
+          v[c] = *reinterpret_cast<const float4*>(gb + e0);
+        } else {
+          if (e0 + 0 < m) v[c].x = gb[e0 + 0];
+          if (e0 + 1 < m) v[c].y = gb[e0 + 1];
+          if (e0 + 2 < m) v[c].z = gb[e0 + 2];
+        }
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < CP; ++c)
+      draw4<true>(base + (uint64_t)c * kStep + l * 4, qc, r[c]);
+
+    // ---- scale of each bucket: reduction over its LPB lanes -------------------------
+    float scale;
+    if (a.norm_mode == 0) {
+      double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll
+      for (int c = 0; c < CP; ++c) {
+        s0 = fma((double)v[c].x, (double)v[c].x, s0);
+        s1 = fma((double)v[c].y, (double)v[c].y, s1);
+        s2 = fma((double)v[c].z, (double)v[c].z, s2);
+        s3 = fma((double)v[c].w, (double)v[c].w, s3);
+      }
+      double ss = (s0 + s1) + (s2 + s3);
+      ss += dpp_fetch_f64<kDppShr1, 0xf>(ss);
+      ss += dpp_fetch_f64<kDppShr2, 0xf>(ss);
+      ss += dpp_fetch_f64<kDppShr4, 0xf>(ss);
+      ss += dpp_fetch_f64<kDppShr8, 0xf>(ss);
+      if (LPB >= 32) ss += dpp_fetch_f64<kDppBcast15, 0xa>(ss);
+      if (LPB >= 64) ss += dpp_fetch_f64<kDppBcast31, 0xc>(ss);
+      scale = (float)sqrt(ss);  // right in the last lane of each bucket
+    } else {
+      float mx = 0.f;
+#pragma unroll
+      for (int c = 0; c < CP; ++c)
+        mx = fmaxf(fmaxf(mx, fmaxf(fabsf(v[c].x), fabsf(v[c].y))),
+                   fmaxf(fabsf(v[c].z), fabsf(v[c].w)));
+      mx = fmaxf(mx, __uint_as_float(dpp_fetch<kDppShr1, 0xf>(__float_as_uint(mx))));
+      mx = fmaxf(mx, __uint_as_float(dpp_fetch<kDppShr2, 0xf>(__float_as_uint(mx))));
+      mx = fmaxf(mx, __uint_as_float(dpp_fetch<kDppShr4, 0xf>(__float_as_uint(mx))));
+      mx = fmaxf(mx, __uint_as_float(dpp_fetch<kDppShr8, 0xf>(__float_as_uint(mx))));
+      if (LPB >= 32) mx = fmaxf(mx, __uint_as_float(dpp_fetch<kDppBcast15, 0xa>(__float_as_uint(mx))));
+      if (LPB >= 64) mx = fmaxf(mx, __uint_as_float(dpp_fetch<kDppBcast31, 0xc>(__float_as_uint(mx))));
+      scale = mx;
+    }
+    scale = __shfl(scale, last_lane, kWave);
+    const float inv = (scale > 0.f) ? s_f / scale : 0.f;
+
+    // ---- quantize, pack, store ------------------------------------------------------------
+    uint32_t* const str = a.payload + (uint64_t)b * a.fixed_words_full;
+    const uint32_t lw = (m * B + 31u) >> 5, sw = (m + 31u) >> 5;
+    uint32_t* const lplane = str + 2;
+    uint32_t* const splane = lplane + lw;
+    uint32_t esc = 0xFFFFFFFFu;
+#pragma unroll
+    for (int c = 0; c < CP; ++c) {
+      const uint32_t e0 = (uint32_t)c * kStep + l * 4;
+      uint32_t z[4];
+      z[0] = quantize_one(v[c].x, inv, s_f, s, r[c][0]);
+      z[1] = quantize_one(v[c].y, inv, s_f, s, r[c][1]);
+      z[2] = quantize_one(v[c].z, inv, s_f, s, r[c][2]);
+      z[3] = quantize_one(v[c].w, inv, s_f, s, r[c][3]);
+      const uint32_t nib = (v[c].x < 0.f ? 1u : 0u) | (v[c].y < 0.f ? 2u : 0u) |
+                           (v[c].z < 0.f ? 4u : 0u) | (v[c].w < 0.f ? 8u : 0u);
+      if (max(max(z[0], z[1]), max(z[2], z[3])) > fmax) {  // level s with s = 2^B: rare
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (z[j] > fmax) { esc = e0 + j; z[j] = fmax; }
+      }
+      if (B == 8) {
+        const uint32_t wi = e0 >> 2;
+        if (all_full || wi < lw) lplane[wi] = z[0] | (z[1] << 8) | (z[2] << 16) | (z[3] << 24);
+      } else if (B == 16) {
+        const uint32_t wi = e0 >> 1;
+        if (all_full || wi < lw) lplane[wi] = z[0] | (z[1] << 16);
+        if (all_full || wi + 1 < lw) lplane[wi + 1] = z[2] | (z[3] << 16);
+      } else if (B == 4) {
+        uint32_t h = z[0] | (z[1] << 4) | (z[2] << 8) | (z[3] << 12);
+        h |= dpp_fetch<kDppShl1, 0xf>(h) << 16;
+        const uint32_t wi = e0 >> 3;
+        if ((l & 1) == 0 && (all_full || wi < lw)) lplane[wi] = h;
+      } else {
+        uint32_t h = z[0] | (z[1] << 2) | (z[2] << 4) | (z[3] << 6);
+        h |= dpp_fetch<kDppShl1, 0xf>(h) << 8;
+        h |= dpp_fetch<kDppShl2, 0xf>(h) << 16;
+        const uint32_t wi = e0 >> 4;
+        if ((l & 3) == 0 && (all_full || wi < lw)) lplane[wi] = h;
+      }
+      uint32_t sg = nib;
+      sg |= dpp_fetch<kDppShl1, 0xf>(sg) << 4;
+      sg |= dpp_fetch<kDppShl2, 0xf>(sg) << 8;
+      sg |= dpp_fetch<kDppShl4, 0xf>(sg) << 16;
+      const uint32_t si = e0 >> 5;
+      if ((l & 7) == 0 && (all_full || si < sw)) splane[si] = sg;
+    }
+    // escape word of each bucket: at most one of its lanes holds an index
+    const uint64_t eb = __ballot(esc != 0xFFFFFFFFu);
+    if (eb) {
+      uint64_t mine = eb;
+      if constexpr (LPB < 64) mine = (eb >> (sb * LPB)) & ((1ull << LPB) - 1ull);
+      const int src = mine ? (int)(sb * LPB) + __ffsll((unsigned long long)mine) - 1 : lane;
+      const uint32_t got = (uint32_t)__shfl((int)esc, src, kWave);
+      esc = mine ? got : 0xFFFFFFFFu;
+    }
+    if (l == 0 && live) {
+      str[0] = __float_as_uint(scale);
+      str[1] = esc;
+    }
+  }
+}
+
 // Moves each team's region to its place in the message: base_j = sum of the
 // totals of the teams before j.  One workgroup per team.
 __global__ __launch_bounds__(256) void k_encode_compact(CompactArgs a) {
@@ -360,6 +523,28 @@ hipError_t launch_encode_bucket(const EncodeArgs& a, uint32_t code, int tw, int 
   if (tw == 2 && cpw == 8) return launch_tw_cpw<2, 8>(a, code, grid, lds, st);
   if (tw == 4 && cpw == 8) return launch_tw_cpw<4, 8>(a, code, grid, lds, st);
   return hipErrorInvalidValue;
+}
+
+template <int LPB, int CP>
+static hipError_t launch_fixed_small_b(const EncodeArgs& a, uint32_t teams, hipStream_t st) {
+  const dim3 grid(teams), block(64);
+  switch (a.fixed_bits) {
+    case 2: hipLaunchKernelGGL((k_encode_fixed_small<LPB, CP, 2>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((k_encode_fixed_small<LPB, CP, 4>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((k_encode_fixed_small<LPB, CP, 8>), grid, block, 0, st, a); break;
+    default: hipLaunchKernelGGL((k_encode_fixed_small<LPB, CP, 16>), grid, block, 0, st, a); break;
+  }
+  return hipGetLastError();
+}
+
+// d <= 1024, d % 4 == 0; a.bper counts groups of 64/lpb buckets per team.
+hipError_t launch_encode_fixed_small(const EncodeArgs& a, int lpb, int cp, uint32_t teams,
+                                     hipStream_t st) {
+  if (lpb == 16 && cp <= 1) return launch_fixed_small_b<16, 1>(a, teams, st);
+  if (lpb == 16 && cp <= 2) return launch_fixed_small_b<16, 2>(a, teams, st);
+  if (lpb == 16) return launch_fixed_small_b<16, 4>(a, teams, st);
+  if (lpb == 32) return launch_fixed_small_b<32, 4>(a, teams, st);
+  return launch_fixed_small_b<64, 4>(a, teams, st);
 }
 
 hipError_t launch_encode_compact(const CompactArgs& a, uint32_t teams, hipStream_t st) {

@@ -104,6 +104,8 @@ struct GenArgs {
 hipError_t launch_encode_bucket(const EncodeArgs& a, uint32_t code, int tw, int cpw,
                                 uint32_t teams, size_t lds, hipStream_t st);
 hipError_t launch_encode_compact(const CompactArgs& a, uint32_t teams, hipStream_t st);
+hipError_t launch_encode_fixed_small(const EncodeArgs& a, int lpb, int cp, uint32_t teams,
+                                     hipStream_t st);
 hipError_t launch_write_empty(uint32_t* header, uint32_t* table, uint32_t code, uint32_t norm,
                               uint32_t s, uint64_t d, uint32_t stream_id, uint32_t iteration,
                               hipStream_t st);
