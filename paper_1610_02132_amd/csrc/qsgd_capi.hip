@@ -237,8 +237,8 @@ int run_decode(const qsgd_params* p, const void* const* msgs_dev, const size_t* 
   uint32_t gw = 1;  // buckets per wavefront: a power of two, gw * K lanes, gw * winp floats
   while (gw * 2 * K <= 64 && gw * 2 <= 16) gw *= 2;
   while (gw > 1 && (g.nb + gw - 1) / gw < (uint64_t)cus * 8) gw /= 2;
-  a.win = win; a.winp = winp; a.gw = gw; a.rec = std::min(16u, 64u / gw);
-  const size_t lds = 4 * ((size_t)gw * winp + 64 * a.rec + 192);
+  a.win = win; a.winp = winp; a.gw = gw; a.rec = kRec;
+  const size_t lds = 4 * ((size_t)gw * winp + 64 * a.rec + 64 * (kStrWin + 1) + 64);
   const uint32_t blocks = (uint32_t)((g.nb + gw - 1) / gw);
   ScopedTiming tm("decode_elias", st);
   if (launch_decode_elias(a, blocks, lds, st) != hipSuccess) return QSGD_ERR_HIP;

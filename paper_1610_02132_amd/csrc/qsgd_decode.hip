@@ -8,13 +8,14 @@
 // parallelism is across strings: every lane of a wavefront reads its own string
 // (bucket g of message k), the wavefront owns gw buckets of all K messages, and
 // the per-bucket offset table says where each string starts.  Records go through
-// small per-string queues in LDS and are applied to an LDS accumulator message
-// by message (k ascending), so the fp32 sum has one fixed order; then the
-// accumulator is streamed against x with float4 accesses.
+// small per-string queues in LDS and are applied to an LDS accumulator such that
+// every element's fp32 sum is the one taken message by message (k ascending);
+// then the accumulator is streamed against x with float4 accesses.
 #include "qsgd_device.hpp"
 #include "qsgd_kernels.hpp"
 
 namespace qsgd {
+
 
 namespace {
 
@@ -56,15 +57,6 @@ __device__ __forceinline__ uint32_t omega_peek(uint32_t w, uint32_t& len) {
   if (!t0) { v = 1u; l = 1u; }
   len = l;
   return v;
-}
-
-// The 32 stream bits that start at bit `bitpos` of a string (bit j = bit 31-j%32 of
-// word j/32).  Words past the end read as zeros.
-__device__ __forceinline__ uint32_t peek_bits(const uint32_t* w, uint32_t nwords, uint32_t bitpos) {
-  const uint32_t wi = bitpos >> 5, off = bitpos & 31u;
-  const uint32_t hi = wi < nwords ? w[wi] : 0u;
-  const uint32_t lo = wi + 1 < nwords ? w[wi + 1] : 0u;
-  return (uint32_t)((((uint64_t)hi << 32) | lo) >> (32u - off));
 }
 
 }  // namespace
@@ -203,25 +195,30 @@ __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
 }
 
 // ---- Elias codes: one lane per string, gw buckets x K messages per wavefront -------
-// Per wavefront: (1) per window of `win` bucket positions the x values are fetched
-// into registers first, so that their latency hides behind the parsing; (2) every
-// lane parses ahead into its own small ring of records, reading its string straight
-// from global memory (L1/L2 resident; staging the strings in LDS was measured
-// slower: the LDS it takes costs more occupancy than the loads cost latency);
-// (3) records are applied to the LDS accumulator in message order, but only up to
-// the position every string has been parsed to; (4) registers and accumulator
-// are combined and stored.  Little LDS per wavefront (small windows) matters more
-// than long windows: the kernel lives on occupancy.
+// The bucket is walked in windows of `win` (<= 256) positions.  Per wavefront:
+//  (1) x of the NEXT window is requested into registers, a whole window ahead of
+//      its use;
+//  (2) every lane parses ahead into its own ring of records.  Its string comes
+//      through a small per-lane ring of words in LDS that is refilled in pieces
+//      (a 128-byte line of a message is then fetched a few times, not once per
+//      code word), and the parser itself works on a 64-bit register of unread bits;
+//  (3) records are applied to an LDS accumulator, but only up to the position
+//      every string has been parsed to, and such that every element's terms are
+//      added in message order (see the apply step below);
+//  (4) registers and accumulator are combined and stored.
+// The kernel is bound by latency and instruction issue, not by bytes: small LDS
+// per wavefront (short rings, 256-position windows) buys occupancy, which
+// measured better than longer rings or windows.
 
 // CODE: sparse or dense Elias code.  LG: groups a level's code word may have.
 template <int CODE, int LG, int NQ>
 __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* acc, uint32_t* queue,
-                                                  uint32_t* counts, uint32_t* heads,
-                                                  float* scales, uint32_t b0, uint32_t gcount) {
+                                                  uint32_t* swin, uint32_t b0, uint32_t gcount) {
   constexpr bool kSparse = CODE == QSGD_CODE_SPARSE;
   // a whole record in one 32-bit peek: gap <= 21 bits, sign, level <= 7 bits
   constexpr bool kNarrow = !kSparse || LG <= 2;
-  const uint32_t K = a.K, gw = a.gw, win = a.win, rec = a.rec, s = a.s;
+  const uint32_t K = a.K, gw = a.gw, win = a.win, s = a.s;
+  constexpr uint32_t rec = kRec;
   constexpr uint32_t winp = kChunk;  // accumulator stride per bucket
   const int lane = threadIdx.x;
   const uint64_t pay = (uint64_t)H_WORDS + a.table_words;
@@ -257,25 +254,67 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     }
     if (!open) flag_corrupt(a.status);
   }
-  scales[lane] = open ? my_scale : 0.f;
+  if (!open) my_scale = 0.f;
+
+  // The lane's view of its string: the last kStrWin words fetched, as a ring in LDS
+  // (word j of the string sits in slot j % kStrWin).  A string is touched once per
+  // kStrFetch words instead of once per record, and the touches of one wavefront
+  // happen together at the top of a round, so a 128-byte line of a message is
+  // pulled from memory a few times rather than once per code word.
+  uint32_t* const slot = swin + (uint32_t)lane * (kStrWin + 1u);
+  uint32_t sfill = 0;   // words [sfill - kStrWin, sfill) of the string are in the ring
+  auto fetch = [&]() {
+    uint32_t t[kStrFetch];
+#pragma unroll
+    for (uint32_t j = 0; j < kStrFetch; ++j) {
+      const uint32_t idx = sfill + j;
+      t[j] = idx < nwords ? str[idx] : 0u;
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < kStrFetch; ++j) slot[(sfill + j) & (kStrWin - 1u)] = t[j];
+    sfill += kStrFetch;
+  };
+  // Word wi of the string (zero past its end), out of the ring.
+  auto ring_word = [&](uint32_t wi) -> uint32_t {
+    while (wi >= sfill) fetch();
+    return slot[wi & (kStrWin - 1u)];
+  };
+  // The unread bits live in a 64-bit register, next bit on top (bit j of the stream
+  // is bit 31-j%32 of word j/32).  Words [0, nwi) have been shifted in, so it
+  // holds 32*nwi - bitpos >= 32 valid bits; word nwi waits in `nextw`, read from
+  // the ring one refill ahead so that its LDS latency is off the parser's critical path.
+  uint64_t bw = 0;
+  uint32_t nwi = 0, nextw = 0;
+  auto consume = [&](uint32_t len) {   // len <= 32
+    bw <<= len;
+    bitpos += len;
+    const uint32_t valid = 32u * nwi - bitpos;
+    if (valid <= 32u) {
+      bw |= (uint64_t)nextw << (32u - valid);
+      ++nwi;
+      nextw = ring_word(nwi);
+    }
+  };
 
   // Reads the next record into pend_*; clears `have` at the end of the string.
   auto advance = [&]() {
     if (kSparse) {
       if (bitpos >= endbit) { have = false; return; }
       uint32_t gl, ll, gap, lev;
-      const uint32_t w = peek_bits(str, nwords, bitpos);
+      const uint32_t w = (uint32_t)(bw >> 32);
       gap = omega_peek<3>(w, gl);
       if (kNarrow) {
         const uint32_t x = w << gl;
         pend_neg = x >> 31;
         lev = omega_peek<LG>(x << 1, ll);
+        consume(gl + 1u + ll);
       } else {
-        const uint32_t x = peek_bits(str, nwords, bitpos + gl);
+        consume(gl);
+        const uint32_t x = (uint32_t)(bw >> 32);
         pend_neg = x >> 31;
         lev = omega_peek<LG>(x << 1, ll);
+        consume(1u + ll);
       }
-      bitpos += gl + 1u + ll;
       pend_pos += gap;
       pend_lev = lev;
       if (gap == 0 || lev == 0 || lev > s || pend_pos > m || bitpos > endbit) {
@@ -285,9 +324,9 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     } else {
       if (pend_pos >= m) { have = false; return; }
       uint32_t ll;
-      const uint32_t w = peek_bits(str, nwords, bitpos);
+      const uint32_t w = (uint32_t)(bw >> 32);
       const uint32_t lev1 = omega_peek<LG>(w << 1, ll);
-      bitpos += 1u + ll;
+      consume(1u + ll);
       pend_neg = w >> 31;
       pend_pos += 1;
       pend_lev = lev1 - 1u;
@@ -297,6 +336,12 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       }
     }
   };
+  if (open) {
+    fetch();
+    bw = ((uint64_t)slot[1] << 32) | slot[2];
+    nwi = 3;
+    nextw = slot[3];
+  }
   if (open) { have = true; advance(); }
 
   for (uint32_t j = lane; j < gw * winp; j += 64) acc[j] = 0.f;
@@ -305,29 +350,50 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   // A window is at most 256 positions (winp = 256): quad q of the x registers is
   // bucket q of this wavefront, lane l holds positions 4l..4l+3 of the window.
   uint32_t qhead = 0, qcnt = 0;            // this lane's ring of queued records
-  const uint32_t g2 = lane / rec, r = lane - g2 * rec;  // apply role: bucket g2, ring slot r
+  uint32_t* const accu = reinterpret_cast<uint32_t*>(acc);
+  const uint32_t grow = (g < gw ? g : 0u) * winp;   // this lane's accumulator row
+  const uint32_t dump = gw * winp + kRec * 64u + 64u * (kStrWin + 1u) + (uint32_t)lane;
   const uint32_t i = (uint32_t)lane * 4u;
-  for (uint32_t ws = 0; ws < a.d; ws += win) {
-    const uint32_t wend = ws + win;  // positions (1-based) up to wend fall in this window
-    // ---- fetch this window of x into registers (latency hides behind the parsing) ----
-    float4 xr[NQ];
+  // x of one window into registers: quad qi is bucket qi of this wavefront.
+  auto load_x = [&](float4 (&dst)[NQ], uint32_t ws) {
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
-      xr[qi] = make_float4(0.f, 0.f, 0.f, 0.f);
+      dst[qi] = make_float4(0.f, 0.f, 0.f, 0.f);
       if ((uint32_t)qi < gcount) {
         const uint64_t base = (uint64_t)(b0 + qi) * a.d;
         const uint32_t mb = (uint32_t)min((uint64_t)a.d, a.n - base);
         const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
         const float* xp = a.x + base + ws + i;
         if (i + 3 < cntw) {
-          xr[qi] = *reinterpret_cast<const float4*>(xp);
+          dst[qi] = *reinterpret_cast<const float4*>(xp);
         } else {
-          if (i + 0 < cntw) xr[qi].x = xp[0];
-          if (i + 1 < cntw) xr[qi].y = xp[1];
-          if (i + 2 < cntw) xr[qi].z = xp[2];
+          if (i + 0 < cntw) dst[qi].x = xp[0];
+          if (i + 1 < cntw) dst[qi].y = xp[1];
+          if (i + 2 < cntw) dst[qi].z = xp[2];
         }
       }
     }
+  };
+  // Order of the memory operations (the wait counter retires them in order): the
+  // x values of window w+1 are requested at the start of window w and used at the
+  // end of window w+1; the strings are topped up at the end of a window, BEFORE
+  // that window's stores, so that waiting for string words never waits for a
+  // store or for the x values requested after them.
+  uint32_t tw[kStrFetch], tw_base = 0;   // string words on their way: [tw_base, tw_base + kStrFetch)
+  bool tw_pending = false;
+  auto commit_pending = [&]() {
+    if (tw_pending && sfill == tw_base) {   // (a fetch on demand may have overtaken them)
+#pragma unroll
+      for (uint32_t j = 0; j < kStrFetch; ++j) slot[(sfill + j) & (kStrWin - 1u)] = tw[j];
+      sfill += kStrFetch;
+    }
+    tw_pending = false;
+  };
+  float4 xr[NQ], xn[NQ];
+  load_x(xr, 0);
+  for (uint32_t ws = 0; ws < a.d; ws += win) {
+    const uint32_t wend = ws + win;  // positions (1-based) up to wend fall in this window
+    if (wend < a.d) load_x(xn, wend);
     // ---- rounds: parse ahead into the rings, apply what is due --------------------------
     // A position may only be applied once EVERY string has been parsed past it,
     // or an element could receive message 5's term before message 2's.  `limit`
@@ -337,41 +403,138 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     // some string is not, all of them fill their rings (fewer, fuller passes of
     // the divergent parse loop).
     for (;;) {
-      if (__ballot(have && pend_pos <= wend) != 0) {
-        while (have && qcnt < rec) {
+      // A parse pass costs as many trips of the divergent loop as its busiest lane
+      // takes, so passes are short and start when most lanes can use all the trips
+      // (their rings have room), or when a lane is out of records for this window.
+      const uint64_t needy = __ballot(have && pend_pos <= wend);
+      const uint32_t nroom = (uint32_t)__popcll(__ballot(have && qcnt + kRoom <= rec));
+      if (needy != 0 || nroom >= kParseLanes) {
+        // top up the string rings together, then parse
+        commit_pending();
+        if (have && sfill < nwords && sfill - nwi <= kStrWin - kStrFetch) fetch();
+        const uint32_t trips = __popcll(needy) >= 32 ? rec : kParse;   // dense data: no imbalance
+        for (uint32_t np = 0; np < trips && have && qcnt < rec; ++np) {
           if (pend_lev) {
-            queue[lane * rec + ((qhead + qcnt) & (rec - 1))] =
+            queue[((qhead + qcnt) & (rec - 1)) * 64u + lane] =
                 (pend_pos - 1u) | (pend_neg << 13) | (pend_lev << 14);
             ++qcnt;
           }
           advance();
         }
       }
-      uint32_t limit = wave_min_u32(have ? pend_pos - 1u : 0xFFFFFFFFu);
+      // At most kApply records per lane are applied in a round: a lane that holds
+      // more caps the limit at its first record beyond them.
+      uint32_t qv[kApply + 1], ad[kApply];
+#pragma unroll
+      for (uint32_t t = 0; t <= kApply; ++t)
+        qv[t] = queue[((qhead + t) & (kRec - 1)) * 64u + lane];
+      const uint32_t cap = qcnt > kApply ? (qv[kApply] & 0x1FFFu) : 0xFFFFFFFFu;
+      uint32_t limit = wave_min_u32(min(have ? pend_pos - 1u : 0xFFFFFFFFu, cap));
       limit = min(limit, wend);   // 0-based positions below `limit` are due
-      counts[lane] = qcnt;
-      heads[lane] = qhead;
+      // ---- apply the due records of this lane's own ring ---------------------------------
+      // All records of one position become due in the same round.  Sums of one or
+      // two terms do not depend on the order of the additions; only positions hit
+      // by three or more messages need the additions in message order.  The
+      // accumulator word itself first counts the position's terms:
+      //   A  every due record adds 1 to its word and learns its arrival rank;
+      //   B  the totals are read back;
+      //   C  arrival 0 stores its term (or 0.0 if the total is above two);
+      //   D  arrival 1 of a two-term position adds its term;
+      //   E  positions with more terms: messages take turns in ascending order.
+      // Every phase handles the ring entries
+      // in groups of kGrp with straight-line code: entries that do not take part
+      // add 0, or write to the lane's dump word, instead of branching, so that the
+      // LDS operations of a group are in flight together.
+      uint32_t due = 0, first = 0, two = 0, many = 0;   // bit t: ring entry t
+#pragma unroll
+      for (uint32_t t = 0; t < kApply; ++t) {
+        const uint32_t p0 = qv[t] & 0x1FFFu;
+        ad[t] = grow + ((p0 - ws) & (winp - 1u));
+        due |= (t < qcnt && p0 < limit ? 1u : 0u) << t;
+      }
+      const uint32_t tmax = 32u - (uint32_t)__clz((int)wave_max_u32(due));  // uniform
+      constexpr uint32_t kGrp = 4;
+#pragma unroll
+      for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
+        if (t0 >= tmax) break;
+        uint32_t rk[kGrp];
+#pragma unroll
+        for (uint32_t j = 0; j < kGrp; ++j) rk[j] = atomicAdd(&accu[ad[t0 + j]], (due >> (t0 + j)) & 1u);
+#pragma unroll
+        for (uint32_t j = 0; j < kGrp; ++j) first |= (rk[j] == 0u ? 1u : 0u) << (t0 + j);
+      }
+      first &= due;
       __syncthreads();
-      for (uint32_t kk = 0; kk < K; ++kk) {
-        if (g2 < gw) {
-          const uint32_t sl = g2 * K + kk;
-          if (r < counts[sl]) {
-            const uint32_t q = queue[sl * rec + ((heads[sl] + r) & (rec - 1))];
-            const uint32_t p0 = q & 0x1FFFu;
-            if (p0 < limit) {
-              const float mag = scales[sl] * (float)(q >> 14);
-              acc[g2 * winp + (p0 - ws)] += ((q >> 13) & 1u) ? -mag : mag;
-            }
+#pragma unroll
+      for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
+        if (t0 >= tmax) break;
+        uint32_t c[kGrp];
+#pragma unroll
+        for (uint32_t j = 0; j < kGrp; ++j) c[j] = accu[ad[t0 + j]];
+#pragma unroll
+        for (uint32_t j = 0; j < kGrp; ++j) {
+          two |= (c[j] == 2u ? 1u : 0u) << (t0 + j);
+          many |= (c[j] > 2u ? 1u : 0u) << (t0 + j);
+        }
+      }
+      two &= due;
+      many &= due;
+      __syncthreads();
+      float term[kApply];
+#pragma unroll
+      for (uint32_t t = 0; t < kApply; ++t) {
+        const float mag = my_scale * (float)(qv[t] >> 14);
+        term[t] = ((qv[t] >> 13) & 1u) ? -mag : mag;
+      }
+#pragma unroll
+      for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
+        if (t0 >= tmax) break;
+#pragma unroll
+        for (uint32_t j = 0; j < kGrp; ++j) {
+          const uint32_t t = t0 + j;
+          acc[((first >> t) & 1u) ? ad[t] : dump] = ((many >> t) & 1u) ? 0.f : term[t];
+        }
+      }
+      __syncthreads();
+      const uint32_t second = two & ~first;
+      if (__ballot(second != 0) != 0) {
+#pragma unroll
+        for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
+          if (t0 >= tmax) break;
+          float old[kGrp];
+#pragma unroll
+          for (uint32_t j = 0; j < kGrp; ++j)
+            old[j] = acc[((second >> (t0 + j)) & 1u) ? ad[t0 + j] : dump];
+#pragma unroll
+          for (uint32_t j = 0; j < kGrp; ++j)
+            acc[((second >> (t0 + j)) & 1u) ? ad[t0 + j] : dump] = old[j] + term[t0 + j];
+        }
+      }
+      if (__ballot(many != 0) != 0) {
+        for (uint32_t kk = 0; kk < K; ++kk) {
+          __syncthreads();
+          if (__ballot(many != 0 && k == kk) == 0) continue;
+          if (k == kk) {
+#pragma unroll
+            for (uint32_t t = 0; t < kApply; ++t)
+              if ((many >> t) & 1u) acc[ad[t]] += term[t];
           }
         }
-        __syncthreads();
       }
-      // drop what was applied from the front of the ring
-      while (qcnt && (queue[lane * rec + qhead] & 0x1FFFu) < limit) {
-        qhead = (qhead + 1u) & (rec - 1);
-        --qcnt;
-      }
+      __syncthreads();
+      const uint32_t ndue = (uint32_t)__popc(due);
+      qhead = (qhead + ndue) & (kRec - 1);
+      qcnt -= ndue;
       if (limit == wend) break;   // uniform: every string is parsed past this window
+    }
+    // ---- string words requested a window ago arrive; request the next ones ---------------
+    commit_pending();
+    tw_pending = have && sfill < nwords && sfill - nwi <= kStrWin - kStrFetch;
+    tw_base = sfill;
+#pragma unroll
+    for (uint32_t j = 0; j < kStrFetch; ++j) {
+      const uint32_t idx = sfill + j;
+      tw[j] = (tw_pending && idx < nwords) ? str[idx] : 0u;
     }
     // ---- combine the accumulator with x and store ------------------------------------
 #pragma unroll
@@ -402,6 +565,8 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
         }
       }
     }
+#pragma unroll
+    for (int qi = 0; qi < NQ; ++qi) xr[qi] = xn[qi];
     __syncthreads();
   }
 }
@@ -410,16 +575,14 @@ template <int CODE, int LG, int NQ>
 __global__ __launch_bounds__(64) void k_decode_elias(DecodeArgs a) {
   if (*a.status != 0) return;
   extern __shared__ uint32_t smem[];
-  // LDS: [acc: gw*winp floats][rings: 64*rec][counts 64][heads 64][scales 64]
+  // LDS: [acc: gw*winp floats][record rings: rec*64][string rings: 64*(kStrWin+1)]
   const uint32_t gw = a.gw, winp = a.winp, rec = a.rec;
   float* const acc = reinterpret_cast<float*>(smem);
   uint32_t* const queue = smem + gw * winp;
-  uint32_t* const counts = queue + 64u * rec;
-  uint32_t* const heads = counts + 64;
-  float* const scales = reinterpret_cast<float*>(counts + 128);
+  uint32_t* const swin = queue + 64u * rec;
   const uint32_t b0 = blockIdx.x * gw;
   const uint32_t gcount = min(gw, a.nb - b0);  // buckets this wavefront really has
-  decode_elias_body<CODE, LG, NQ>(a, acc, queue, counts, heads, scales, b0, gcount);
+  decode_elias_body<CODE, LG, NQ>(a, acc, queue, swin, b0, gcount);
 }
 
 hipError_t launch_decode_check(const DecodeArgs& a, hipStream_t st) {

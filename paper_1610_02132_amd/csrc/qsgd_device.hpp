@@ -164,6 +164,17 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+// Max over the 64 lanes, returned to every lane.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  v = max(v, dpp_fetch<kDppShr1, 0xf>(v));
+  v = max(v, dpp_fetch<kDppShr2, 0xf>(v));
+  v = max(v, dpp_fetch<kDppShr4, 0xf>(v));
+  v = max(v, dpp_fetch<kDppShr8, 0xf>(v));
+  v = max(v, dpp_fetch<kDppBcast15, 0xa>(v));
+  v = max(v, dpp_fetch<kDppBcast31, 0xc>(v));
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 // Inclusive prefix sum over the 64 lanes.
 __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int /*lane*/) {
   v += dpp_fetch<kDppShr1, 0xf>(v);

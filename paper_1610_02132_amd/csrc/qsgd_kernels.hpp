@@ -10,6 +10,31 @@ namespace qsgd {
 
 constexpr uint32_t kMaxBucketFast = 8192;  // largest bucket the register path holds
 constexpr uint32_t kMaxTeams = 8192;       // most teams (regions) one encode uses
+#ifndef QSGD_STR_WIN
+#define QSGD_STR_WIN 8
+#endif
+constexpr uint32_t kStrWin = QSGD_STR_WIN;  // Elias decode: words of a string a lane keeps in LDS
+#ifndef QSGD_REC
+#define QSGD_REC 16
+#endif
+constexpr uint32_t kRec = QSGD_REC;               // Elias decode: records a lane queues ahead
+#ifndef QSGD_APPLY
+#define QSGD_APPLY 8
+#endif
+constexpr uint32_t kApply = QSGD_APPLY;              // Elias decode: records a lane applies per round
+#ifndef QSGD_PARSE
+#define QSGD_PARSE 8
+#endif
+#ifndef QSGD_PARSE_LANES
+#define QSGD_PARSE_LANES 32
+#endif
+#ifndef QSGD_ROOM
+#define QSGD_ROOM QSGD_PARSE
+#endif
+constexpr uint32_t kRoom = QSGD_ROOM;        // ring slots a lane must have free to count as "has room"
+constexpr uint32_t kParse = QSGD_PARSE;      // Elias decode: trips of a short parse pass
+constexpr uint32_t kParseLanes = QSGD_PARSE_LANES;  // lanes with room that start a pass
+constexpr uint32_t kStrFetch = kStrWin / 2; // words fetched at a time
 
 struct EncodeArgs {
   const float* g;
