@@ -26,6 +26,32 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def hbm_traffic(workload: str, n: int) -> dict:
+    """HBM bytes per launch of each kernel, as measured with the hardware counters.
+
+    They cannot be collected from inside this process; they come from the committed
+    summary of two `rocprofv3 --pmc` runs of this same command (FETCH_SIZE, then
+    WRITE_SIZE, each scaled by what the counter reads for the copy kernel of known
+    size that this script also launches).  The summary is only used for the
+    workload and size it was taken on; otherwise traffic is reported as null.
+    """
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    out = {}
+    try:
+        with open(path) as f:
+            lines = f.read().splitlines()
+    except OSError:
+        return out
+    size_ok = False
+    for line in lines:
+        tok = line.split()
+        if len(tok) == 2 and tok[0] == "n":
+            size_ok = int(tok[1]) == n
+        elif len(tok) == 4 and tok[0] == "kernel" and size_ok:
+            out[tok[1]] = float(tok[2]) + float(tok[3])   # fetched + written bytes
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -138,9 +164,10 @@ def main() -> int:
     else:
         dom, dom_alg = dec_main, dec_alg
     achieved = dom_alg / (kern[dom]["ms_avg"] * 1e-3) / 1e9
+    traffic = hbm_traffic(w.name, n)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": None, "bytes_per_launch": dom_alg,
+                "traffic": traffic.get(dom), "bytes_per_launch": dom_alg,
                 "avg_launch_ms": round(kern[dom]["ms_avg"], 4)}
     other, other_alg = (dec_main, dec_alg) if dom == enc_main else (enc_main, enc_alg)
     roofline_other = None
@@ -148,20 +175,25 @@ def main() -> int:
         a2 = other_alg / (kern[other]["ms_avg"] * 1e-3) / 1e9
         roofline_other = {"bound": "hbm", "kernel": other, "achieved": round(a2, 1),
                           "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                          "frac": round(a2 / HBM_PEAK_GBPS, 4), "bytes_per_launch": other_alg,
+                          "frac": round(a2 / HBM_PEAK_GBPS, 4), "traffic": traffic.get(other),
+                          "bytes_per_launch": other_alg,
                           "avg_launch_ms": round(kern[other]["ms_avg"], 4)}
 
-    # ---- plain copy ceiling of this machine, for context -------------------------------------
+    # ---- plain copy ceiling of this machine, for context (the library's float4 copy kernel) ----
     src = grads[0]
     dst = torch.empty_like(src)
     for _ in range(2):
-        dst.copy_(src)
+        q.qsgd_copy_probe(dst, src)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    q.qsgd_timing_reset()
+    q.qsgd_timing_enable(True)
     for _ in range(5):
-        dst.copy_(src)
+        q.qsgd_copy_probe(dst, src)
     torch.cuda.synchronize()
-    copy_gbps = 5 * 8.0 * n / (time.perf_counter() - t0) / 1e9
+    q.qsgd_timing_enable(False)
+    copy_ms, copy_cnt = q.qsgd_timing_get("copy_probe")
+    q.qsgd_timing_reset()
+    copy_gbps = copy_cnt * 8.0 * n / (copy_ms * 1e-3) / 1e9
     del dst
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload ------------

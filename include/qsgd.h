@@ -154,6 +154,14 @@ int qsgd_timing_enable(int on);
 int qsgd_timing_reset(void);
 int qsgd_timing_get(const char *prefix, double *total_ms, uint64_t *launches);
 
+/* Measurement aid, not part of the method: a plain copy kernel (16-byte loads and
+ * stores, grid-stride) of `bytes` bytes (a multiple of 16) from src_dev to dst_dev,
+ * both device pointers aligned to 16 bytes, on `hip_stream`.  It gives the copy
+ * ceiling of the machine the codec is compared with, and a kernel of known HBM
+ * traffic that hardware counters can be calibrated against.  Timed as "copy_probe".
+ * Returns 0, QSGD_ERR_INVALID_ARG or QSGD_ERR_HIP. */
+int qsgd_copy_probe(void *dst_dev, const void *src_dev, size_t bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

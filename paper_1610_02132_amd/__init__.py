@@ -8,6 +8,6 @@ has not been built (``python -m paper_1610_02132_amd.build``).
 from .binding import (  # noqa: F401
     CODE_DENSE, CODE_FIXED, CODE_SPARSE, NORM_L2, NORM_MAX, QSGD_MAX_PEERS, Params, QsgdError,
     lib_path, qsgd_decode_accumulate, qsgd_encode, qsgd_max_encoded_bytes, qsgd_message_info,
-    qsgd_message_status, qsgd_sgd_step, qsgd_strerror, qsgd_timing_enable, qsgd_timing_get,
+    qsgd_copy_probe, qsgd_message_status, qsgd_sgd_step, qsgd_strerror, qsgd_timing_enable, qsgd_timing_get,
     qsgd_timing_reset, qsgd_version, qsgd_workspace_bytes, qsgd_workspace_status,
 )

@@ -17,7 +17,7 @@ EXPORTS = [
     "qsgd_version", "qsgd_strerror", "qsgd_max_encoded_bytes", "qsgd_workspace_bytes",
     "qsgd_encode", "qsgd_decode_accumulate", "qsgd_sgd_step", "qsgd_message_info",
     "qsgd_message_status", "qsgd_workspace_status", "qsgd_timing_enable",
-    "qsgd_timing_reset", "qsgd_timing_get",
+    "qsgd_timing_reset", "qsgd_timing_get", "qsgd_copy_probe",
 ]
 
 
@@ -92,6 +92,8 @@ def _load():
     L.qsgd_timing_reset.restype = C.c_int
     L.qsgd_timing_get.argtypes = [C.c_char_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     L.qsgd_timing_get.restype = C.c_int
+    L.qsgd_copy_probe.argtypes = [vp, vp, sz, vp]
+    L.qsgd_copy_probe.restype = C.c_int
     _lib = L
     return L
 
@@ -226,3 +228,14 @@ def qsgd_timing_get(prefix: str):
     if rc:
         raise QsgdError(rc, "qsgd_timing_get")
     return float(ms.value), int(cnt.value)
+
+
+def qsgd_copy_probe(dst, src, stream=None) -> None:
+    """Plain device copy of src into dst (same byte size, a multiple of 16)."""
+    dp, db = _dev(dst, "dst")
+    sp, sb = _dev(src, "src")
+    if db != sb:
+        raise ValueError("dst and src differ in size")
+    rc = _load().qsgd_copy_probe(dp, sp, sb, _stream(stream))
+    if rc:
+        raise QsgdError(rc, "qsgd_copy_probe")

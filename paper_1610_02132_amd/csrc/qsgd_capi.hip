@@ -226,7 +226,7 @@ int run_decode(const qsgd_params* p, const void* const* msgs_dev, const size_t* 
   }
 
   if (g.code == QSGD_CODE_FIXED) {
-    const uint32_t blocks = (uint32_t)std::min<uint64_t>((g.nb + 3) / 4, (uint64_t)cus * 16);
+    const uint32_t blocks = (uint32_t)std::min<uint64_t>((g.nb + 3) / 4, (uint64_t)cus * QSGD_FIXED_BPC);
     ScopedTiming tm("decode_fixed", st);
     if (launch_decode_fixed(a, blocks, st) != hipSuccess) return QSGD_ERR_HIP;
     return QSGD_OK;
@@ -246,6 +246,15 @@ int run_decode(const qsgd_params* p, const void* const* msgs_dev, const size_t* 
 }
 
 }  // namespace
+
+// Plain copy, for calibration and as the machine's copy ceiling.
+__global__ __launch_bounds__(256) void k_copy_probe(float4* __restrict__ dst,
+                                                    const float4* __restrict__ src,
+                                                    uint64_t quads) {
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < quads;
+       i += (uint64_t)gridDim.x * 256)
+    dst[i] = src[i];
+}
 
 extern "C" {
 
@@ -469,6 +478,24 @@ int qsgd_timing_reset(void) {
   for (auto& t : g_launches) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
   g_launches.clear();
   return QSGD_OK;
+}
+
+int qsgd_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream) {
+  if (!dst_dev || !src_dev || (bytes & 15u) || !aligned16(dst_dev) || !aligned16(src_dev))
+    return QSGD_ERR_INVALID_ARG;
+  if (bytes == 0) return QSGD_OK;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    return QSGD_ERR_HIP;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const uint64_t quads = bytes / 16;
+  const uint32_t blocks = (uint32_t)std::min<uint64_t>((quads + 255) / 256, (uint64_t)cus * 16);
+  ScopedTiming tm("copy_probe", st);
+  hipLaunchKernelGGL(k_copy_probe, dim3(blocks), dim3(256), 0, st,
+                     reinterpret_cast<float4*>(dst_dev), reinterpret_cast<const float4*>(src_dev),
+                     quads);
+  return hipGetLastError() == hipSuccess ? QSGD_OK : QSGD_ERR_HIP;
 }
 
 int qsgd_timing_get(const char* prefix, double* total_ms, uint64_t* launches) {

@@ -81,22 +81,26 @@ __global__ void k_decode_check(DecodeArgs a) {
 }
 
 // ---- fixed width: one wavefront per bucket ----------------------------------------
-// Lane k < K keeps message k's scale and escape index.  The level and sign words of
-// KG messages are requested together so that enough bytes are in flight per
-// wavefront; the sum over the messages runs in k order in registers.
-constexpr int kFixedGroup = 8;
-
-template <int B>
+// Lane k < K keeps message k's scale and escape index.  A wavefront takes CH chunks
+// of 256 positions at a time; for those it requests the level and sign words of
+// KG messages together, so that enough bytes are in flight per wavefront, and so
+// that the 128-byte lines of a message that two chunks (or the header and the
+// first chunk) share are touched at one time instead of once per chunk with 15
+// other messages in between (measured: the second touch came from memory again).
+// The sum over the messages runs in k order in registers.
+// CHECK: a field can hold a level above s (s + 1 is not a power of two).
+template <int B, int CH, bool CHECK>
 __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
   if (*a.status != 0) return;
+  constexpr int KG = CH >= 4 ? QSGD_FIXED_KG / 2 : QSGD_FIXED_KG;  // messages whose words are requested together
   const int lane = threadIdx.x & 63;
   const uint32_t wave_global = blockIdx.x * 4 + (threadIdx.x >> 6);
   const uint32_t wave_count = gridDim.x * 4;
   const uint32_t s = a.s, K = a.K;
   const float s_f = (float)s;
   constexpr uint32_t fmask = (1u << B) - 1u;
-  constexpr int LW = B == 16 ? 2 : 1;       // level words a lane reads per message
-  const bool check_range = fmask > s;       // a field can hold a level above s
+  constexpr int LW = B == 16 ? 2 : 1;       // level words a lane reads per message and chunk
+  const uint64_t all_ok = K >= 64 ? ~0ull : ((1ull << K) - 1ull);
 
   for (uint32_t b = wave_global; b < a.nb; b += wave_count) {
     const uint64_t base = (uint64_t)b * a.d;
@@ -115,80 +119,122 @@ __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
       if (!my_ok) { flag_corrupt(a.status); my_scale = 0.f; my_esc = 0xFFFFFFFFu; }
     }
     const uint64_t okmask = __ballot(my_ok != 0);
-    for (uint32_t e0 = lane * 4; e0 < m; e0 += kChunk) {
-      float* xp = a.x + base + e0;
-      const bool full = e0 + 3 < m;
-      float4 xv = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (full) {
-        xv = *reinterpret_cast<const float4*>(xp);
-      } else {
-        xv.x = xp[0];
-        if (e0 + 1 < m) xv.y = xp[1];
-        if (e0 + 2 < m) xv.z = xp[2];
-      }
-      float acc[4] = {0.f, 0.f, 0.f, 0.f};
-      const uint32_t li = (e0 * B) >> 5, si = e0 >> 5, ssh = e0 & 31u;
-      for (uint32_t k0 = 0; k0 < K; k0 += kFixedGroup) {
-        uint32_t wl[kFixedGroup][LW], ws[kFixedGroup];
+    // every message is intact and every chunk of the group is complete: no per-load tests
+    const bool whole = okmask == all_ok && m % (CH * kChunk) == 0;
+    for (uint32_t g0 = 0; g0 < m; g0 += CH * kChunk) {
+      float4 xv[CH];
+      float acc[CH][4];
 #pragma unroll
-        for (int t = 0; t < kFixedGroup; ++t) {
-          const uint32_t k = k0 + t;
-          wl[t][0] = 0; ws[t] = 0;
-          if (LW == 2) wl[t][LW - 1] = 0;
-          if (k < K && ((okmask >> k) & 1ull)) {
-            const uint32_t* lplane = a.msgs[k] + str_off + 2;
-            wl[t][0] = lplane[li];
-            if (LW == 2 && li + 1 < lw) wl[t][LW - 1] = lplane[li + 1];
-            ws[t] = lplane[lw + si];
+      for (int c = 0; c < CH; ++c) {
+        const uint32_t e0 = g0 + (uint32_t)c * kChunk + (uint32_t)lane * 4u;
+        const float* xp = a.x + base + e0;
+        xv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
+        if (e0 + 3 < m) {
+          xv[c] = *reinterpret_cast<const float4*>(xp);
+        } else if (e0 < m) {
+          xv[c].x = xp[0];
+          if (e0 + 1 < m) xv[c].y = xp[1];
+          if (e0 + 2 < m) xv[c].z = xp[2];
+        }
+      }
+      for (uint32_t k0 = 0; k0 < K; k0 += KG) {
+        uint32_t wl[KG][CH][LW], ws[KG][CH];
+        if (whole) {
+#pragma unroll
+          for (int t = 0; t < KG; ++t) {
+            const uint32_t* lplane = a.msgs[min(k0 + t, K - 1u)] + str_off + 2;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+              const uint32_t e0 = g0 + (uint32_t)c * kChunk + (uint32_t)lane * 4u;
+              const uint32_t li = (e0 * B) >> 5;
+              wl[t][c][0] = lplane[li];
+              if (LW == 2) wl[t][c][LW - 1] = lplane[li + 1];
+              ws[t][c] = lplane[lw + (e0 >> 5)];
+            }
+          }
+        } else {
+#pragma unroll
+          for (int t = 0; t < KG; ++t) {
+            const uint32_t k = k0 + t;
+            const bool live = k < K && ((okmask >> k) & 1ull);
+            const uint32_t* lplane = live ? a.msgs[k] + str_off + 2 : nullptr;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+              const uint32_t e0 = g0 + (uint32_t)c * kChunk + (uint32_t)lane * 4u;
+              const uint32_t li = (e0 * B) >> 5;
+              wl[t][c][0] = 0; ws[t][c] = 0;
+              if (LW == 2) wl[t][c][LW - 1] = 0;
+              if (live && e0 < m) {
+                wl[t][c][0] = lplane[li];
+                if (LW == 2 && li + 1 < lw) wl[t][c][LW - 1] = lplane[li + 1];
+                ws[t][c] = lplane[lw + (e0 >> 5)];
+              }
+            }
           }
         }
 #pragma unroll
-        for (int t = 0; t < kFixedGroup; ++t) {
+        for (int t = 0; t < KG; ++t) {
           const uint32_t k = k0 + t;
           if (k >= K) break;
           const float sc = __uint_as_float(lane_bcast(__float_as_uint(my_scale), (int)k));
           const uint32_t esc = lane_bcast(my_esc, (int)k);
-          uint32_t z[4];
-          if (B == 8) {
-            z[0] = wl[t][0] & 0xFFu; z[1] = (wl[t][0] >> 8) & 0xFFu;
-            z[2] = (wl[t][0] >> 16) & 0xFFu; z[3] = wl[t][0] >> 24;
-          } else if (B == 16) {
-            z[0] = wl[t][0] & 0xFFFFu; z[1] = wl[t][0] >> 16;
-            z[2] = wl[t][LW - 1] & 0xFFFFu; z[3] = wl[t][LW - 1] >> 16;
-          } else {
-            const uint32_t w = wl[t][0] >> ((e0 * B) & 31u);
-            z[0] = w & fmask; z[1] = (w >> B) & fmask; z[2] = (w >> (2 * B)) & fmask;
-            z[3] = (w >> (3 * B)) & fmask;
-          }
-          if (esc != 0xFFFFFFFFu) {  // wave-uniform: this message has a top-level value here
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-              if (esc == e0 + j) z[j] = s;
-          }
-          if (check_range) {
-            if (z[0] > s || z[1] > s || z[2] > s || z[3] > s) flag_corrupt(a.status);
-          }
-          const uint32_t sg = ws[t] >> ssh;
+          for (int c = 0; c < CH; ++c) {
+            const uint32_t c0 = g0 + (uint32_t)c * kChunk;       // uniform
+            const uint32_t e0 = c0 + (uint32_t)lane * 4u;
+            uint32_t z[4];
+            if (B == 8) {
+              z[0] = wl[t][c][0] & 0xFFu; z[1] = (wl[t][c][0] >> 8) & 0xFFu;
+              z[2] = (wl[t][c][0] >> 16) & 0xFFu; z[3] = wl[t][c][0] >> 24;
+            } else if (B == 16) {
+              z[0] = wl[t][c][0] & 0xFFFFu; z[1] = wl[t][c][0] >> 16;
+              z[2] = wl[t][c][LW - 1] & 0xFFFFu; z[3] = wl[t][c][LW - 1] >> 16;
+            } else {
+              const uint32_t w = wl[t][c][0] >> ((e0 * B) & 31u);
+              z[0] = w & fmask; z[1] = (w >> B) & fmask; z[2] = (w >> (2 * B)) & fmask;
+              z[3] = (w >> (3 * B)) & fmask;
+            }
+            float mag[4];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            // sign bit into the product: (-0 for a zero level adds like +0)
-            const uint32_t mag = __float_as_uint(sc * (float)z[j]);
-            acc[j] += __uint_as_float(mag ^ ((sg << (31 - j)) & 0x80000000u));
+            for (int j = 0; j < 4; ++j) mag[j] = sc * (float)z[j];
+            // rare, wave-uniform: this message's top-level value lies in this chunk
+            if (esc - c0 < kChunk) {
+              const float top = sc * s_f;
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                if (esc == e0 + j) mag[j] = top;
+            }
+            if (CHECK) {
+              if (max(max(z[0], z[1]), max(z[2], z[3])) > s) flag_corrupt(a.status);
+            }
+            const uint32_t sg = ws[t][c] >> (e0 & 31u);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              // the sign bit goes into the product (-0 for a zero level adds like +0)
+              acc[c][j] += __uint_as_float(((sg << (31 - j)) & 0x80000000u) | __float_as_uint(mag[j]));
+            }
           }
         }
       }
-      if (a.step) {
-        xv.x = fmaf(-a.c, acc[0], xv.x); xv.y = fmaf(-a.c, acc[1], xv.y);
-        xv.z = fmaf(-a.c, acc[2], xv.z); xv.w = fmaf(-a.c, acc[3], xv.w);
-      } else {
-        xv.x += acc[0]; xv.y += acc[1]; xv.z += acc[2]; xv.w += acc[3];
-      }
-      if (full) {
-        *reinterpret_cast<float4*>(xp) = xv;
-      } else {
-        xp[0] = xv.x;
-        if (e0 + 1 < m) xp[1] = xv.y;
-        if (e0 + 2 < m) xp[2] = xv.z;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const uint32_t e0 = g0 + (uint32_t)c * kChunk + (uint32_t)lane * 4u;
+        float* xp = a.x + base + e0;
+        float4 v = xv[c];
+        if (a.step) {
+          v.x = fmaf(-a.c, acc[c][0], v.x); v.y = fmaf(-a.c, acc[c][1], v.y);
+          v.z = fmaf(-a.c, acc[c][2], v.z); v.w = fmaf(-a.c, acc[c][3], v.w);
+        } else {
+          v.x += acc[c][0]; v.y += acc[c][1]; v.z += acc[c][2]; v.w += acc[c][3];
+        }
+        if (e0 + 3 < m) {
+          *reinterpret_cast<float4*>(xp) = v;
+        } else if (e0 < m) {
+          xp[0] = v.x;
+          if (e0 + 1 < m) xp[1] = v.y;
+          if (e0 + 2 < m) xp[2] = v.z;
+        }
       }
     }
   }
@@ -590,14 +636,28 @@ hipError_t launch_decode_check(const DecodeArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <int CH, bool CHECK>
+static void launch_fixed_ch(const DecodeArgs& a, dim3 grid, dim3 block, hipStream_t st) {
+  switch (a.fixed_bits) {
+    case 2: hipLaunchKernelGGL((k_decode_fixed<2, CH, CHECK>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((k_decode_fixed<4, CH, CHECK>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((k_decode_fixed<8, CH, CHECK>), grid, block, 0, st, a); break;
+    default: hipLaunchKernelGGL((k_decode_fixed<16, CH, CHECK>), grid, block, 0, st, a); break;
+  }
+}
+
+template <bool CHECK>
+static void launch_fixed_check(const DecodeArgs& a, dim3 grid, dim3 block, hipStream_t st) {
+  if (a.d <= kChunk) launch_fixed_ch<1, CHECK>(a, grid, block, st);
+  else if (a.d <= 2 * kChunk) launch_fixed_ch<2, CHECK>(a, grid, block, st);
+  else launch_fixed_ch<4, CHECK>(a, grid, block, st);
+}
+
 hipError_t launch_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t st) {
   const dim3 grid(blocks), block(256);
-  switch (a.fixed_bits) {
-    case 2: hipLaunchKernelGGL(k_decode_fixed<2>, grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL(k_decode_fixed<4>, grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL(k_decode_fixed<8>, grid, block, 0, st, a); break;
-    default: hipLaunchKernelGGL(k_decode_fixed<16>, grid, block, 0, st, a); break;
-  }
+  const bool check = ((1ull << a.fixed_bits) - 1ull) > a.s;
+  if (check) launch_fixed_check<true>(a, grid, block, st);
+  else launch_fixed_check<false>(a, grid, block, st);
   return hipGetLastError();
 }
 

@@ -10,6 +10,12 @@ namespace qsgd {
 
 constexpr uint32_t kMaxBucketFast = 8192;  // largest bucket the register path holds
 constexpr uint32_t kMaxTeams = 8192;       // most teams (regions) one encode uses
+#ifndef QSGD_FIXED_BPC
+#define QSGD_FIXED_BPC 128  // fixed-width decode: workgroups per compute unit
+#endif
+#ifndef QSGD_FIXED_KG
+#define QSGD_FIXED_KG 8     // fixed-width decode: messages requested together
+#endif
 #ifndef QSGD_STR_WIN
 #define QSGD_STR_WIN 8
 #endif
