@@ -506,12 +506,13 @@ static int open_msg(const void *msg, size_t bytes, view *v) {
   return QO_OK;
 }
 
-static int bucket_extent(const view *v, uint64_t b, uint64_t *off, uint64_t *cnt) {
+static int bucket_extent_m(const view *v, uint64_t b, uint64_t m, uint64_t *off,
+                           uint64_t *cnt) {
   if (b >= v->nb) return QO_ERR_INVALID_ARG;
   if (v->p.code == QO_CODE_FIXED) {
     uint64_t full = (bucket_max_bits(&v->p, v->d) + 31) / 32;
     *off = b * full;
-    *cnt = (bucket_max_bits(&v->p, bucket_len(&v->p, b)) + 31) / 32;
+    *cnt = (bucket_max_bits(&v->p, m) + 31) / 32;
   } else {
     uint64_t o0 = v->table[b], o1 = v->table[b + 1];
     if (o1 < o0) return QO_ERR_CORRUPT;
@@ -520,6 +521,11 @@ static int bucket_extent(const view *v, uint64_t b, uint64_t *off, uint64_t *cnt
   }
   if (*off + *cnt > v->pw) return QO_ERR_CORRUPT;
   return QO_OK;
+}
+
+static int bucket_extent(const view *v, uint64_t b, uint64_t *off, uint64_t *cnt) {
+  if (b >= v->nb) return QO_ERR_INVALID_ARG;
+  return bucket_extent_m(v, b, bucket_len(&v->p, b), off, cnt);
 }
 
 int qo_message_info(const void *msg, size_t avail_bytes, qo_params *p,
@@ -558,10 +564,10 @@ int qo_payload_offset(const void *msg, size_t bytes, uint64_t *byte_off) {
 
 /* Reads bucket b back into (norm, levels[m], neg[m]); neg is only meaningful
  * where a sign was sent (sparse code: nonzero levels). */
-static int decode_bucket(const view *v, uint64_t b, float *norm, uint32_t *levels,
-                         uint8_t *neg) {
-  uint64_t off, cnt, m = bucket_len(&v->p, b);
-  int rc = bucket_extent(v, b, &off, &cnt);
+static int decode_bucket_m(const view *v, uint64_t b, uint64_t m, float *norm,
+                           uint32_t *levels, uint8_t *neg) {
+  uint64_t off, cnt;
+  int rc = bucket_extent_m(v, b, m, &off, &cnt);
   if (rc) return rc;
   if (cnt < 1) return QO_ERR_CORRUPT;
   const uint32_t *w = v->payload + off;
@@ -622,6 +628,12 @@ static int decode_bucket(const view *v, uint64_t b, float *norm, uint32_t *level
     }
   }
   return QO_OK;
+}
+
+static int decode_bucket(const view *v, uint64_t b, float *norm, uint32_t *levels,
+                         uint8_t *neg) {
+  if (b >= v->nb) return QO_ERR_INVALID_ARG;
+  return decode_bucket_m(v, b, bucket_len(&v->p, b), norm, levels, neg);
 }
 
 int qo_decode_tuple(const void *msg, size_t bytes, uint32_t *levels, uint8_t *neg,
@@ -732,4 +744,226 @@ int qo_sgd_step(const void *const *msgs, const size_t *bytes, uint32_t K, float 
   for (uint32_t k = 0; k < K; ++k) free(dec[k]);
   free(dec);
   return QO_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Tensor-aware messages (Sec. 5, "Protocol": matrices with fewer than 10K      */
+/* elements are not quantized; quantization buckets are laid out per matrix).  */
+/*                                                                             */
+/* The gradient is an arena of p->n floats in which tensor j occupies           */
+/* [offset_j, offset_j + size_j).  A tensor with size < bypass_below goes into  */
+/* the message as raw fp32; any other tensor is cut into buckets of d values    */
+/* that restart at the tensor's first value (its last bucket is shorter), so    */
+/* no bucket mixes two tensors' scales.  Draws are indexed by arena position.   */
+/* Message (version 2): header as before with nb = number of such buckets and  */
+/* payload words = strings + raw words; offset table (Elias codes); bucket      */
+/* strings in tensor order; then the raw tensors in tensor order.               */
+/* ------------------------------------------------------------------------- */
+
+static int layout_check(const qo_params *p, const qo_tensor *t, uint32_t T) {
+  int rc = check_params(p);
+  if (rc) return rc;
+  if (T && !t) return QO_ERR_INVALID_ARG;
+  uint64_t prev_end = 0;
+  for (uint32_t j = 0; j < T; ++j) { /* ascending, disjoint, inside the arena */
+    if (t[j].offset < prev_end || t[j].size > p->n || t[j].offset > p->n - t[j].size)
+      return QO_ERR_INVALID_ARG;
+    prev_end = t[j].offset + t[j].size;
+  }
+  return QO_OK;
+}
+
+int qo_layout_counts(const qo_params *p, const qo_tensor *t, uint32_t T,
+                     uint64_t bypass_below, uint64_t *buckets, uint64_t *raw_elems) {
+  int rc = layout_check(p, t, T);
+  if (rc) return rc;
+  uint64_t nb = 0, raw = 0;
+  for (uint32_t j = 0; j < T; ++j) {
+    if (t[j].size < bypass_below) raw += t[j].size;
+    else nb += (t[j].size + p->d - 1) / p->d;
+  }
+  if (buckets) *buckets = nb;
+  if (raw_elems) *raw_elems = raw;
+  return QO_OK;
+}
+
+static uint64_t layout_table_words(const qo_params *p, uint64_t nb) {
+  if (p->code == QO_CODE_FIXED) return 0;
+  return (nb + 1 + 3) & ~(uint64_t)3;
+}
+
+size_t qo_layout_max_encoded_bytes(const qo_params *p, const qo_tensor *t, uint32_t T,
+                                   uint64_t bypass_below) {
+  uint64_t nb, raw;
+  if (qo_layout_counts(p, t, T, bypass_below, &nb, &raw)) return 0;
+  uint64_t words = 0, full = (bucket_max_bits(p, p->d) + 31) / 32;
+  for (uint32_t j = 0; j < T; ++j) {
+    if (t[j].size < bypass_below) continue;
+    uint64_t q = t[j].size / p->d, r = t[j].size % p->d;
+    words += q * full;
+    if (r) words += p->code == QO_CODE_FIXED ? full : (bucket_max_bits(p, r) + 31) / 32;
+  }
+  return (size_t)(4 * (H_WORDS + layout_table_words(p, nb) + words + raw));
+}
+
+int qo_encode_layout(const qo_params *p, const qo_tensor *t, uint32_t T,
+                     uint64_t bypass_below, const float *arena, void *msg,
+                     size_t capacity, size_t *bytes_out) {
+  uint64_t nb, raw;
+  int rc = qo_layout_counts(p, t, T, bypass_below, &nb, &raw);
+  if (rc) return rc;
+  uint64_t d = p->d, tw = layout_table_words(p, nb);
+  if (capacity < 4 * (H_WORDS + tw)) return QO_ERR_CAPACITY;
+  uint32_t *w = (uint32_t *)msg;
+  memset(w, 0, capacity - capacity % 4);
+  uint32_t *table = w + H_WORDS;
+  uint32_t *payload = table + tw;
+  uint64_t cap_words = capacity / 4 - H_WORDS - tw;
+  uint64_t full = (bucket_max_bits(p, d) + 31) / 32;
+
+  uint32_t *levels = (uint32_t *)malloc(d * sizeof(uint32_t));
+  uint8_t *neg = (uint8_t *)malloc(d);
+  if (!levels || !neg) { free(levels); free(neg); return QO_ERR_INVALID_ARG; }
+  bitw bw = {payload, cap_words * 32, 0, 0};
+  uint64_t b = 0;
+  for (uint32_t j = 0; j < T && rc == QO_OK; ++j) {
+    if (t[j].size < bypass_below) continue;
+    for (uint64_t o = 0; o < t[j].size; o += d, ++b) {
+      uint64_t m = t[j].size - o < d ? t[j].size - o : d;
+      uint64_t start = t[j].offset + o;
+      float norm;
+      quantize_bucket(p, arena + start, m, start, NULL, levels, neg, &norm, NULL, NULL);
+      if (tw) table[b] = (uint32_t)(bw.pos / 32);
+      else bw.pos = b * full * 32; /* fixed width: bucket b sits at b * words(full bucket) */
+      code_bucket(p, m, norm, levels, neg, &bw);
+      bw.pos = (bw.pos + 31) & ~(uint64_t)31;
+      if (bw.overflow || bw.pos > bw.cap) { rc = QO_ERR_CAPACITY; break; }
+    }
+  }
+  free(levels);
+  free(neg);
+  if (rc) return rc;
+  uint64_t strings = tw ? bw.pos / 32 : nb * full;
+  if (tw) table[nb] = (uint32_t)strings;
+  if (strings + raw > cap_words) return QO_ERR_CAPACITY;
+  uint64_t r = 0;
+  for (uint32_t j = 0; j < T; ++j) { /* the small tensors, as they are */
+    if (t[j].size >= bypass_below) continue;
+    memcpy(payload + strings + r, arena + t[j].offset, t[j].size * 4);
+    r += t[j].size;
+  }
+  uint64_t pw = strings + raw;
+  w[H_MAGIC] = QO_MAGIC; w[H_VERSION] = 2; w[H_CODE] = p->code; w[H_NORM] = p->norm;
+  w[H_S] = p->s; w[H_STREAM] = p->stream_id;
+  w[H_D_LO] = (uint32_t)d; w[H_D_HI] = (uint32_t)(d >> 32);
+  w[H_N_LO] = (uint32_t)p->n; w[H_N_HI] = (uint32_t)(p->n >> 32);
+  w[H_NB_LO] = (uint32_t)nb; w[H_NB_HI] = (uint32_t)(nb >> 32);
+  w[H_PW_LO] = (uint32_t)pw; w[H_PW_HI] = (uint32_t)(pw >> 32);
+  w[H_STATUS] = 0; w[H_ITER] = p->iteration;
+  if (bytes_out) *bytes_out = (size_t)(4 * (H_WORDS + tw + pw));
+  return QO_OK;
+}
+
+/* Values of one message at their arena positions; positions outside every
+ * tensor are left as they are. */
+int qo_decode_layout(const qo_tensor *t, uint32_t T, uint64_t bypass_below,
+                     const void *msg, size_t bytes, float *arena_out) {
+  if (!msg || bytes < 4 * H_WORDS) return QO_ERR_CORRUPT;
+  const uint32_t *w = (const uint32_t *)msg;
+  if (w[H_MAGIC] != QO_MAGIC || w[H_VERSION] != 2 || w[H_STATUS] != 0) return QO_ERR_CORRUPT;
+  view v;
+  memset(&v, 0, sizeof v);
+  v.p.code = w[H_CODE]; v.p.norm = w[H_NORM]; v.p.s = w[H_S];
+  v.p.stream_id = w[H_STREAM]; v.p.iteration = w[H_ITER];
+  v.p.d = w[H_D_LO] | ((uint64_t)w[H_D_HI] << 32);
+  v.p.n = w[H_N_LO] | ((uint64_t)w[H_N_HI] << 32);
+  uint64_t nb, raw;
+  if (qo_layout_counts(&v.p, t, T, bypass_below, &nb, &raw)) return QO_ERR_CORRUPT;
+  if ((w[H_NB_LO] | ((uint64_t)w[H_NB_HI] << 32)) != nb) return QO_ERR_CORRUPT;
+  v.d = v.p.d; v.nb = nb;
+  v.tw = layout_table_words(&v.p, nb);
+  v.pw = w[H_PW_LO] | ((uint64_t)w[H_PW_HI] << 32);
+  if ((uint64_t)bytes / 4 < H_WORDS + v.tw + v.pw) return QO_ERR_CORRUPT;
+  v.table = w + H_WORDS;
+  v.payload = v.table + v.tw;
+  uint64_t full = (bucket_max_bits(&v.p, v.d) + 31) / 32;
+  uint64_t strings = v.tw ? v.table[nb] : nb * full;
+  if (strings + raw != v.pw) return QO_ERR_CORRUPT;
+
+  uint32_t *lv = (uint32_t *)malloc(v.d * sizeof(uint32_t));
+  uint8_t *ng = (uint8_t *)malloc(v.d);
+  if (!lv || !ng) { free(lv); free(ng); return QO_ERR_INVALID_ARG; }
+  int rc = QO_OK;
+  uint64_t b = 0, r = 0;
+  for (uint32_t j = 0; j < T && rc == QO_OK; ++j) {
+    if (t[j].size < bypass_below) {
+      memcpy(arena_out + t[j].offset, v.payload + strings + r, t[j].size * 4);
+      r += t[j].size;
+      continue;
+    }
+    for (uint64_t o = 0; o < t[j].size && rc == QO_OK; o += v.d, ++b) {
+      uint64_t m = t[j].size - o < v.d ? t[j].size - o : v.d;
+      float norm;
+      rc = decode_bucket_m(&v, b, m, &norm, lv, ng);
+      if (rc) break;
+      float scale = norm / (float)v.p.s;
+      float *out = arena_out + t[j].offset + o;
+      for (uint64_t i = 0; i < m; ++i) {
+        float mag = scale * (float)lv[i];
+        out[i] = (lv[i] != 0 && ng[i]) ? -mag : mag;
+      }
+    }
+  }
+  free(lv);
+  free(ng);
+  return rc;
+}
+
+/* acc_i <- acc_i + sum_l (message l at i)   (step == 0), or
+ * x_i <- fma(-(eta/K), sum_l (message l at i), x_i)   (Algorithm 1, last line),
+ * over the positions that belong to a tensor; the sum runs over l ascending. */
+static int layout_reduce(const qo_tensor *t, uint32_t T, uint64_t bypass_below,
+                         const void *const *msgs, const size_t *bytes, uint32_t K,
+                         int step, float eta, float *x) {
+  if (K < 1 || !msgs || !bytes || bytes[0] < 4 * H_WORDS) return QO_ERR_INVALID_ARG;
+  const uint32_t *w0 = (const uint32_t *)msgs[0];
+  uint64_t n = w0[H_N_LO] | ((uint64_t)w0[H_N_HI] << 32);
+  float **dec = (float **)calloc(K, sizeof(float *));
+  if (!dec) return QO_ERR_INVALID_ARG;
+  int rc = QO_OK;
+  for (uint32_t k = 0; k < K && rc == QO_OK; ++k) {
+    const uint32_t *wk = (const uint32_t *)msgs[k];
+    if (bytes[k] < 4 * H_WORDS || (wk[H_N_LO] | ((uint64_t)wk[H_N_HI] << 32)) != n) {
+      rc = QO_ERR_INVALID_ARG;
+      break;
+    }
+    dec[k] = (float *)calloc(n ? n : 1, sizeof(float));
+    if (!dec[k]) { rc = QO_ERR_INVALID_ARG; break; }
+    rc = qo_decode_layout(t, T, bypass_below, msgs[k], bytes[k], dec[k]);
+  }
+  if (rc == QO_OK) {
+    float c = eta / (float)K;
+    for (uint32_t j = 0; j < T; ++j) {
+      for (uint64_t i = t[j].offset; i < t[j].offset + t[j].size; ++i) {
+        float sum = 0.0f;
+        for (uint32_t k = 0; k < K; ++k) sum += dec[k][i];
+        x[i] = step ? fmaf(-c, sum, x[i]) : x[i] + sum;
+      }
+    }
+  }
+  for (uint32_t k = 0; k < K; ++k) free(dec[k]);
+  free(dec);
+  return rc;
+}
+
+int qo_decode_accumulate_layout(const qo_tensor *t, uint32_t T, uint64_t bypass_below,
+                                const void *const *msgs, const size_t *bytes, uint32_t K,
+                                float *acc) {
+  return layout_reduce(t, T, bypass_below, msgs, bytes, K, 0, 0.0f, acc);
+}
+
+int qo_sgd_step_layout(const qo_tensor *t, uint32_t T, uint64_t bypass_below,
+                       const void *const *msgs, const size_t *bytes, uint32_t K, float eta,
+                       float *x) {
+  return layout_reduce(t, T, bypass_below, msgs, bytes, K, 1, eta, x);
 }

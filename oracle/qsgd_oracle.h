@@ -141,6 +141,31 @@ int qo_bucket_extent(const void *msg, size_t bytes, uint64_t b, uint64_t *word_o
 /* Byte offset of the payload inside the message. */
 int qo_payload_offset(const void *msg, size_t bytes, uint64_t *byte_off);
 
+/* ---- tensor-aware messages (Sec. 5, "Protocol": small matrices are not
+ * quantized, buckets are laid out per matrix).  The gradient is an arena of
+ * p->n floats; tensor j occupies [offset, offset + size), tensors ascending and
+ * disjoint.  Tensors with size < bypass_below travel as raw fp32; the others
+ * are cut into buckets of p->d values that restart at the tensor's first value.
+ * Draws are indexed by arena position.  CONTAINER LAYOUT: PARITY UNPINNED (the
+ * paper fixes only the rule, not a format); the quantized values are pinned
+ * through the flat functions they reuse. */
+typedef struct { uint64_t offset, size; } qo_tensor;
+int qo_layout_counts(const qo_params *p, const qo_tensor *t, uint32_t T,
+                     uint64_t bypass_below, uint64_t *buckets, uint64_t *raw_elems);
+size_t qo_layout_max_encoded_bytes(const qo_params *p, const qo_tensor *t, uint32_t T,
+                                   uint64_t bypass_below);
+int qo_encode_layout(const qo_params *p, const qo_tensor *t, uint32_t T,
+                     uint64_t bypass_below, const float *arena, void *msg,
+                     size_t capacity, size_t *bytes_out);
+int qo_decode_layout(const qo_tensor *t, uint32_t T, uint64_t bypass_below,
+                     const void *msg, size_t bytes, float *arena_out);
+int qo_decode_accumulate_layout(const qo_tensor *t, uint32_t T, uint64_t bypass_below,
+                                const void *const *msgs, const size_t *bytes, uint32_t K,
+                                float *acc);
+int qo_sgd_step_layout(const qo_tensor *t, uint32_t T, uint64_t bypass_below,
+                       const void *const *msgs, const size_t *bytes, uint32_t K, float eta,
+                       float *x);
+
 #ifdef __cplusplus
 }
 #endif

@@ -108,6 +108,19 @@ def lib():
         L.qo_bucket_extent.restype = C.c_int
         L.qo_payload_offset.argtypes = [vp, sz, u64p]
         L.qo_payload_offset.restype = C.c_int
+        u32 = C.c_uint32
+        L.qo_layout_counts.argtypes = [PP, vp, u32, C.c_uint64, u64p, u64p]
+        L.qo_layout_counts.restype = C.c_int
+        L.qo_layout_max_encoded_bytes.argtypes = [PP, vp, u32, C.c_uint64]
+        L.qo_layout_max_encoded_bytes.restype = sz
+        L.qo_encode_layout.argtypes = [PP, vp, u32, C.c_uint64, vp, vp, sz, C.POINTER(sz)]
+        L.qo_encode_layout.restype = C.c_int
+        L.qo_decode_layout.argtypes = [vp, u32, C.c_uint64, vp, sz, vp]
+        L.qo_decode_layout.restype = C.c_int
+        L.qo_decode_accumulate_layout.argtypes = [vp, u32, C.c_uint64, vp, vp, u32, vp]
+        L.qo_decode_accumulate_layout.restype = C.c_int
+        L.qo_sgd_step_layout.argtypes = [vp, u32, C.c_uint64, vp, vp, u32, C.c_float, vp]
+        L.qo_sgd_step_layout.restype = C.c_int
         _lib = L
     return _lib
 
@@ -324,3 +337,62 @@ def bucket_words(msg: np.ndarray, b: int) -> np.ndarray:
     off, cnt = bucket_extent(msg, b)
     base = payload_offset_words(msg)
     return np.asarray(msg[base + off: base + off + cnt])
+
+
+# ---- tensor-aware messages: tensors = [(offset, size), ...] inside an arena of p.n floats ----
+
+def _tensors(tensors) -> np.ndarray:
+    t = np.ascontiguousarray(np.asarray(tensors, dtype=np.uint64).reshape(-1, 2))
+    return t
+
+
+def layout_counts(p: Params, tensors, bypass_below: int):
+    """(number of quantization buckets, number of raw fp32 values)."""
+    t = _tensors(tensors)
+    nb, raw = C.c_uint64(0), C.c_uint64(0)
+    cp = p.c()
+    _chk(lib().qo_layout_counts(C.byref(cp), _ptr(t), len(t), bypass_below, C.byref(nb),
+                                C.byref(raw)), "layout_counts")
+    return int(nb.value), int(raw.value)
+
+
+def encode_layout(p: Params, tensors, bypass_below: int, arena,
+                  capacity: int | None = None) -> np.ndarray:
+    t = _tensors(tensors)
+    arena = _f32(arena)
+    assert arena.size == p.n
+    cp = p.c()
+    cap = int(lib().qo_layout_max_encoded_bytes(C.byref(cp), _ptr(t), len(t), bypass_below)) \
+        if capacity is None else capacity
+    msg = np.zeros((cap + 3) // 4, dtype=np.uint32)
+    used = C.c_size_t(0)
+    _chk(lib().qo_encode_layout(C.byref(cp), _ptr(t), len(t), bypass_below, _ptr(arena),
+                                _ptr(msg), cap, C.byref(used)), "encode_layout")
+    return msg[: used.value // 4].copy()
+
+
+def decode_layout(tensors, bypass_below: int, msg, n: int) -> np.ndarray:
+    t = _tensors(tensors)
+    msg = np.ascontiguousarray(msg, dtype=np.uint32)
+    out = np.zeros(max(n, 1), dtype=np.float32)
+    _chk(lib().qo_decode_layout(_ptr(t), len(t), bypass_below, _ptr(msg), msg.nbytes, _ptr(out)),
+         "decode_layout")
+    return out[:n]
+
+
+def decode_accumulate_layout(tensors, bypass_below: int, msgs, acc) -> np.ndarray:
+    t = _tensors(tensors)
+    keep, ptrs, sizes = _msg_arrays(msgs)
+    acc = _f32(acc).copy()
+    _chk(lib().qo_decode_accumulate_layout(_ptr(t), len(t), bypass_below, ptrs, sizes, len(keep),
+                                           _ptr(acc)), "decode_accumulate_layout")
+    return acc
+
+
+def sgd_step_layout(tensors, bypass_below: int, msgs, eta: float, x) -> np.ndarray:
+    t = _tensors(tensors)
+    keep, ptrs, sizes = _msg_arrays(msgs)
+    x = _f32(x).copy()
+    _chk(lib().qo_sgd_step_layout(_ptr(t), len(t), bypass_below, ptrs, sizes, len(keep),
+                                  C.c_float(eta), _ptr(x)), "sgd_step_layout")
+    return x
