@@ -59,6 +59,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c5", help="c1..c5 (default c5: n=1e9, s=4, d=8192, K=16)")
     ap.add_argument("--n", type=int, default=0, help="shrink the workload to n elements (debug)")
+    ap.add_argument("--layout", action="store_true",
+                    help="tensor-aware messages: the workload's tensors in an arena, tensors "
+                         "below --bypass elements sent raw, buckets restart at every tensor")
+    ap.add_argument("--bypass", type=int, default=10_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="target CPU time of the oracle baseline sample")
@@ -84,22 +88,62 @@ def main() -> int:
     K, n = w.K, w.n
     log(f"workload {w.name}: n={n} s={w.s} d={w.d} code={w.code} K={K} ({w.note})")
 
+    # tensor-aware mode: the tensors sit in an arena, each at a multiple of 4 elements
+    tensors, n_values = None, n
+    if args.layout:
+        tensors, off = [], 0
+        for size in w.tensors:
+            tensors.append((off, size))
+            off += (size + 3) // 4 * 4
+        n = off          # arena length; n_values = elements that belong to a tensor
+        layout = q.Layout(tensors, min(w.d, 8192), args.bypass)
+        nb_l, raw_l, _ = q.qsgd_layout_info(layout)
+        log(f"layout: {len(tensors)} tensors in an arena of {n}; {nb_l} buckets, {raw_l} raw values")
+
     def params(k):
         return q.Params(n=n, s=w.s, d=w.d, code=w.code, seed=w.seed, stream_id=k, iteration=0)
 
+    def to_arena(flat):
+        if not args.layout:
+            return flat
+        a = torch.zeros(n, dtype=torch.float32, device="cuda")
+        o = 0
+        for off_, size in tensors:
+            a[off_:off_ + size] = flat[o:o + size]
+            o += size
+        return a
+
     # ---- inputs, resident in HBM ------------------------------------------------
     t0 = time.time()
-    grads = [W.gradient(w, k, device="cuda") for k in range(K)]
-    x = W.parameters(w, device="cuda")
+    grads = [to_arena(W.gradient(w, k, device="cuda")) for k in range(K)]
+    x = to_arena(W.parameters(w, device="cuda"))
     torch.cuda.synchronize()
     log(f"inputs generated in {time.time() - t0:.1f}s "
         f"({(K + 1) * 4 * n / 2**30:.1f} GiB resident)")
 
-    ws = torch.empty(q.qsgd_workspace_bytes(params(0), K) // 4, dtype=torch.int32, device="cuda")
+    if args.layout:
+        ws_bytes = q.qsgd_layout_workspace_bytes(params(0), layout, K)
+        cap_max = q.qsgd_layout_max_encoded_bytes(params(0), layout)
+
+        def encode(k, msg):
+            q.qsgd_encode_layout(params(k), layout, grads[k], msg, ws)
+
+        def step():
+            q.qsgd_sgd_step_layout(params(0), layout, msgs, w.eta, x, ws)
+    else:
+        ws_bytes = q.qsgd_workspace_bytes(params(0), K)
+        cap_max = q.qsgd_max_encoded_bytes(params(0))
+
+        def encode(k, msg):
+            q.qsgd_encode(params(k), grads[k], msg, ws)
+
+        def step():
+            q.qsgd_sgd_step(params(0), msgs, w.eta, x, ws)
+
+    ws = torch.empty(ws_bytes // 4, dtype=torch.int32, device="cuda")
     # size the message buffers from a first encode into a worst-case buffer
-    cap_max = q.qsgd_max_encoded_bytes(params(0))
     probe = torch.empty(cap_max // 4, dtype=torch.int32, device="cuda")
-    q.qsgd_encode(params(0), grads[0], probe, ws)
+    encode(0, probe)
     status, total0 = q.qsgd_message_status(probe)
     assert status == 0, status
     del probe
@@ -109,8 +153,8 @@ def main() -> int:
 
     def one_step():
         for k in range(K):
-            q.qsgd_encode(params(k), grads[k], msgs[k], ws)
-        q.qsgd_sgd_step(params(0), msgs, w.eta, x, ws)
+            encode(k, msgs[k])
+        step()
 
     for _ in range(max(args.warmup, 1)):   # at least one untimed pass fills the messages
         one_step()
@@ -136,11 +180,12 @@ def main() -> int:
     assert q.qsgd_workspace_status(ws) == 0
 
     ms_per_step = 1e3 * elapsed / args.steps
+    n_arena, n = n, n_values      # throughput counts the values that belong to a tensor
     value = 4.0 * K * n * args.steps / elapsed / 1e9
 
     kern = {}
-    for name in ("encode_bucket", "encode_compact", "encode_general", "decode_check",
-                 "decode_fixed", "decode_elias", "decode_general"):
+    for name in ("encode_bucket", "encode_compact", "encode_general", "encode_raw", "decode_check",
+                 "decode_raw", "decode_fixed", "decode_elias", "decode_general"):
         ms, cnt = q.qsgd_timing_get(name)
         if cnt:
             kern[name] = {"ms_total": ms, "launches": cnt, "ms_avg": ms / cnt}
@@ -164,7 +209,7 @@ def main() -> int:
     else:
         dom, dom_alg = dec_main, dec_alg
     achieved = dom_alg / (kern[dom]["ms_avg"] * 1e-3) / 1e9
-    traffic = hbm_traffic(w.name, n)
+    traffic = {} if args.layout else hbm_traffic(w.name, n)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": traffic.get(dom), "bytes_per_launch": dom_alg,
@@ -193,12 +238,35 @@ def main() -> int:
     q.qsgd_timing_enable(False)
     copy_ms, copy_cnt = q.qsgd_timing_get("copy_probe")
     q.qsgd_timing_reset()
-    copy_gbps = copy_cnt * 8.0 * n / (copy_ms * 1e-3) / 1e9
+    copy_gbps = copy_cnt * 8.0 * n_arena / (copy_ms * 1e-3) / 1e9
     del dst
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload ------------
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.layout:
+        from oracle import qsgd_oracle as qo
+
+        def run_oracle_layout(T):   # the first T tensors of the arena
+            sub = tensors[:T]
+            na = sub[-1][0] + sub[-1][1]
+            gs = [grads[k][:na].cpu().numpy() for k in range(K)]
+            xs = x[:na].cpu().numpy()
+            t0 = time.perf_counter()
+            ms_ = [qo.encode_layout(qo.Params(n=na, s=w.s, d=w.d, code=w.code, seed=w.seed,
+                                              stream_id=k), sub, args.bypass, gs[k])
+                   for k in range(K)]
+            qo.sgd_step_layout(sub, args.bypass, ms_, w.eta, xs)
+            return sum(t[1] for t in sub), time.perf_counter() - t0
+
+        T, (ns, t_cpu) = 1, run_oracle_layout(1)
+        while T < len(tensors) and t_cpu < 0.25 * args.cpu_seconds:
+            T = min(len(tensors), 2 * T)
+            ns, t_cpu = run_oracle_layout(T)
+        cpu = {"value": round(4.0 * K * ns / t_cpu / 1e9, 5), "unit": "GB/s", "cores": 1,
+               "kind": "oracle",
+               "sample": f"first {T} tensors ({ns} elements) of each of the {K} gradients: {K} x "
+                         f"encode + 1 x decode+step, {t_cpu:.1f} s single-threaded"}
+    elif not args.no_cpu_baseline:
         from oracle import qsgd_oracle as qo
         d_eff = min(w.d, n)
 
@@ -227,7 +295,9 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: n={n}, s={w.s}, d={w.d}, "
-                               f"code={['sparse Elias', 'dense Elias', 'fixed width'][w.code]}, K={K}",
+                               f"code={['sparse Elias', 'dense Elias', 'fixed width'][w.code]}, K={K}"
+                               + (f", tensor-aware ({len(tensors)} tensors, raw below {args.bypass})"
+                                  if args.layout else ""),
                    "n": n, "s": w.s, "d": w.d, "K": K, "eta": w.eta,
                    "bits_per_element": round(8 * msg_bytes_avg / n, 4),
                    "message_bytes": int(msg_bytes_avg)},

@@ -131,6 +131,46 @@ int qsgd_sgd_step(const qsgd_params *p, const void *const *msgs_dev,
                   const size_t *msg_bytes, uint32_t K, float eta, float *x_dev,
                   void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
+/* ---- Tensor-aware messages (Sec. 5, "Protocol": matrices with fewer than 10K
+ * elements are sent unquantized, and quantization buckets are laid out per matrix).
+ *
+ * The gradient (and x) is an ARENA of p->n floats on the device in which tensor j
+ * occupies [offsets[j], offsets[j] + sizes[j]); tensors ascend, do not overlap, and
+ * start at multiples of 4 elements (16 bytes), as tensors packed with allocator
+ * alignment do.  A tensor with sizes[j] < bypass_below travels as raw fp32 behind
+ * the bucket strings; every other tensor is cut into buckets of d values that
+ * restart at its first value (its last bucket is shorter), so no bucket mixes two
+ * tensors' scales.  Draws are indexed by arena position.  Messages carry header
+ * version 2; decoding needs the same layout.  d must be a multiple of 4, <= 8192.
+ *
+ * qsgd_layout_create builds the layout from HOST arrays and uploads two small tables
+ * to the current device (it allocates device memory; the layout is immutable and may
+ * be shared by any number of calls on that device); qsgd_layout_destroy frees it.
+ * The other calls mirror their flat namesakes: same arguments plus the layout, same
+ * ownership, same error behaviour; p->d must equal the layout's d and p->n must
+ * cover its extent.  Positions of the arena outside every tensor are never read or
+ * written.  Returns QSGD_ERR_UNSUPPORTED for bucket sizes the layout path does not
+ * take. */
+typedef struct qsgd_layout qsgd_layout;
+int qsgd_layout_create(const uint64_t *offsets, const uint64_t *sizes, uint32_t T, uint64_t d,
+                       uint64_t bypass_below, qsgd_layout **out);
+void qsgd_layout_destroy(qsgd_layout *layout);
+int qsgd_layout_info(const qsgd_layout *layout, uint64_t *buckets, uint64_t *raw_values,
+                     uint64_t *extent);
+size_t qsgd_layout_max_encoded_bytes(const qsgd_params *p, const qsgd_layout *layout);
+size_t qsgd_layout_workspace_bytes(const qsgd_params *p, const qsgd_layout *layout, uint32_t K);
+int qsgd_encode_layout(const qsgd_params *p, const qsgd_layout *layout, const float *g_dev,
+                       void *msg_dev, size_t msg_capacity, void *workspace_dev,
+                       size_t workspace_bytes, void *hip_stream);
+int qsgd_decode_accumulate_layout(const qsgd_params *p, const qsgd_layout *layout,
+                                  const void *const *msgs_dev, const size_t *msg_bytes,
+                                  uint32_t K, float *acc_dev, void *workspace_dev,
+                                  size_t workspace_bytes, void *hip_stream);
+int qsgd_sgd_step_layout(const qsgd_params *p, const qsgd_layout *layout,
+                         const void *const *msgs_dev, const size_t *msg_bytes, uint32_t K,
+                         float eta, float *x_dev, void *workspace_dev, size_t workspace_bytes,
+                         void *hip_stream);
+
 /* Reads a message header from a HOST copy of (at least) its first 64 bytes.
  * Fills *out (seed is not stored: 0) and *total_bytes (either may be NULL).
  * Returns 0, QSGD_ERR_CORRUPT (not a header), or the status the encoder left

@@ -10,4 +10,6 @@ from .binding import (  # noqa: F401
     lib_path, qsgd_decode_accumulate, qsgd_encode, qsgd_max_encoded_bytes, qsgd_message_info,
     qsgd_copy_probe, qsgd_message_status, qsgd_sgd_step, qsgd_strerror, qsgd_timing_enable, qsgd_timing_get,
     qsgd_timing_reset, qsgd_version, qsgd_workspace_bytes, qsgd_workspace_status,
+    Layout, qsgd_decode_accumulate_layout, qsgd_encode_layout, qsgd_layout_info,
+    qsgd_layout_max_encoded_bytes, qsgd_layout_workspace_bytes, qsgd_sgd_step_layout,
 )

@@ -18,6 +18,9 @@ EXPORTS = [
     "qsgd_encode", "qsgd_decode_accumulate", "qsgd_sgd_step", "qsgd_message_info",
     "qsgd_message_status", "qsgd_workspace_status", "qsgd_timing_enable",
     "qsgd_timing_reset", "qsgd_timing_get", "qsgd_copy_probe",
+    "qsgd_layout_create", "qsgd_layout_destroy", "qsgd_layout_info",
+    "qsgd_layout_max_encoded_bytes", "qsgd_layout_workspace_bytes", "qsgd_encode_layout",
+    "qsgd_decode_accumulate_layout", "qsgd_sgd_step_layout",
 ]
 
 
@@ -94,6 +97,24 @@ def _load():
     L.qsgd_timing_get.restype = C.c_int
     L.qsgd_copy_probe.argtypes = [vp, vp, sz, vp]
     L.qsgd_copy_probe.restype = C.c_int
+    u64p = C.POINTER(C.c_uint64)
+    L.qsgd_layout_create.argtypes = [u64p, u64p, C.c_uint32, C.c_uint64, C.c_uint64,
+                                     C.POINTER(vp)]
+    L.qsgd_layout_create.restype = C.c_int
+    L.qsgd_layout_destroy.argtypes = [vp]
+    L.qsgd_layout_destroy.restype = None
+    L.qsgd_layout_info.argtypes = [vp, u64p, u64p, u64p]
+    L.qsgd_layout_info.restype = C.c_int
+    L.qsgd_layout_max_encoded_bytes.argtypes = [PP, vp]
+    L.qsgd_layout_max_encoded_bytes.restype = sz
+    L.qsgd_layout_workspace_bytes.argtypes = [PP, vp, C.c_uint32]
+    L.qsgd_layout_workspace_bytes.restype = sz
+    L.qsgd_encode_layout.argtypes = [PP, vp, vp, vp, sz, vp, sz, vp]
+    L.qsgd_encode_layout.restype = C.c_int
+    L.qsgd_decode_accumulate_layout.argtypes = [PP, vp, vp, vp, C.c_uint32, vp, vp, sz, vp]
+    L.qsgd_decode_accumulate_layout.restype = C.c_int
+    L.qsgd_sgd_step_layout.argtypes = [PP, vp, vp, vp, C.c_uint32, C.c_float, vp, vp, sz, vp]
+    L.qsgd_sgd_step_layout.restype = C.c_int
     _lib = L
     return L
 
@@ -239,3 +260,92 @@ def qsgd_copy_probe(dst, src, stream=None) -> None:
     rc = _load().qsgd_copy_probe(dp, sp, sb, _stream(stream))
     if rc:
         raise QsgdError(rc, "qsgd_copy_probe")
+
+
+class Layout:
+    """Handle of a qsgd_layout: tensors = [(offset, size), ...] in elements of the arena."""
+
+    def __init__(self, tensors, d: int, bypass_below: int):
+        T = len(tensors)
+        offs = (C.c_uint64 * max(T, 1))(*[int(t[0]) for t in tensors])
+        sizes = (C.c_uint64 * max(T, 1))(*[int(t[1]) for t in tensors])
+        h = C.c_void_p(0)
+        rc = _load().qsgd_layout_create(offs, sizes, T, d, bypass_below, C.byref(h))
+        if rc:
+            raise QsgdError(rc, "qsgd_layout_create")
+        self.handle = h
+        self.d = d
+        self.bypass_below = bypass_below
+        self.tensors = [(int(t[0]), int(t[1])) for t in tensors]
+
+    def close(self) -> None:
+        if self.handle:
+            _load().qsgd_layout_destroy(self.handle)
+            self.handle = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def qsgd_layout_info(layout: Layout):
+    """(buckets, raw values, extent of the arena the tensors use)."""
+    nb, raw, ext = C.c_uint64(0), C.c_uint64(0), C.c_uint64(0)
+    rc = _load().qsgd_layout_info(layout.handle, C.byref(nb), C.byref(raw), C.byref(ext))
+    if rc:
+        raise QsgdError(rc, "qsgd_layout_info")
+    return int(nb.value), int(raw.value), int(ext.value)
+
+
+def qsgd_layout_max_encoded_bytes(p: Params, layout: Layout) -> int:
+    cp = p.c()
+    return int(_load().qsgd_layout_max_encoded_bytes(C.byref(cp), layout.handle))
+
+
+def qsgd_layout_workspace_bytes(p: Params, layout: Layout, K: int) -> int:
+    cp = p.c()
+    return int(_load().qsgd_layout_workspace_bytes(C.byref(cp), layout.handle, K))
+
+
+def qsgd_encode_layout(p: Params, layout: Layout, g, msg, workspace, stream=None) -> None:
+    """Queues the tensor-aware Encode of the arena g -> msg."""
+    if g.dtype.itemsize != 4 or not g.dtype.is_floating_point or g.numel() != p.n:
+        raise ValueError("g must hold n float32")
+    gp, _ = _dev(g, "g")
+    mp, mbytes = _dev(msg, "msg")
+    wp, wbytes = _dev(workspace, "workspace")
+    cp = p.c()
+    rc = _load().qsgd_encode_layout(C.byref(cp), layout.handle, gp, mp, mbytes, wp, wbytes,
+                                    _stream(stream))
+    if rc:
+        raise QsgdError(rc, "qsgd_encode_layout")
+
+
+def qsgd_decode_accumulate_layout(p: Params, layout: Layout, msgs, acc, workspace, msg_bytes=None,
+                                  stream=None) -> None:
+    if acc.numel() != p.n or acc.dtype.itemsize != 4:
+        raise ValueError("acc must hold n float32")
+    ptrs, sizes, K = _msgs(msgs, msg_bytes)
+    ap, _ = _dev(acc, "acc")
+    wp, wbytes = _dev(workspace, "workspace")
+    cp = p.c()
+    rc = _load().qsgd_decode_accumulate_layout(C.byref(cp), layout.handle, ptrs, sizes, K, ap, wp,
+                                               wbytes, _stream(stream))
+    if rc:
+        raise QsgdError(rc, "qsgd_decode_accumulate_layout")
+
+
+def qsgd_sgd_step_layout(p: Params, layout: Layout, msgs, eta: float, x, workspace, msg_bytes=None,
+                         stream=None) -> None:
+    if x.numel() != p.n or x.dtype.itemsize != 4:
+        raise ValueError("x must hold n float32")
+    ptrs, sizes, K = _msgs(msgs, msg_bytes)
+    xp, _ = _dev(x, "x")
+    wp, wbytes = _dev(workspace, "workspace")
+    cp = p.c()
+    rc = _load().qsgd_sgd_step_layout(C.byref(cp), layout.handle, ptrs, sizes, K, C.c_float(eta),
+                                      xp, wp, wbytes, _stream(stream))
+    if rc:
+        raise QsgdError(rc, "qsgd_sgd_step_layout")

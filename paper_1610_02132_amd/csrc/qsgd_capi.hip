@@ -1,10 +1,12 @@
 // C ABI of libqsgd (see include/qsgd.h): parameter checks, geometry, kernel
-// launches.  No device memory is allocated here; scratch is the caller's.
+// launches.  Scratch is the caller's; the only device memory allocated here is the two
+// small tables of a tensor layout (qsgd_layout_create).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstring>
 #include <mutex>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -12,6 +14,23 @@
 #include "qsgd_device.hpp"
 #include "qsgd_encode_wave.hpp"
 #include "qsgd_kernels.hpp"
+
+// Tensor-aware messages: where the tensors sit in the arena, which of them are
+// quantized (and the buckets they are cut into) and which travel raw.  The tables
+// live on the device the layout was created on.
+struct qsgd_layout {
+  uint64_t d = 0, bypass = 0;
+  uint64_t extent = 0;        // one past the last arena position a tensor uses
+  uint64_t nb = 0;            // quantization buckets
+  uint64_t short_buckets = 0; // buckets with fewer than d values ...
+  uint64_t short_values = 0;  // ... and the values in them
+  uint64_t raw = 0;           // raw fp32 values
+  uint32_t R = 0;             // raw tensors
+  int device = 0;
+  uint2* btab = nullptr;      // per bucket: (start / 4, length)
+  uint4* rtab = nullptr;      // per raw tensor: (start / 4, length, offset in the raw section, 0)
+  std::vector<uint32_t> short_len;  // lengths of the short buckets (size accounting)
+};
 
 namespace {
 
@@ -179,16 +198,49 @@ struct ScopedTiming {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int run_decode(const qsgd_params* p, const void* const* msgs_dev, const size_t* msg_bytes,
-               uint32_t K, float c, uint32_t step, float* x_dev, void* ws, size_t ws_bytes,
-               void* hip_stream) {
-  Geometry g;
+// Geometry of a tensor-aware message: the layout says how many buckets there are.
+int layout_geometry(const qsgd_params* p, const qsgd_layout* L, Geometry& g) {
   int rc = make_geometry(p, g);
   if (rc) return rc;
+  if (!L) return QSGD_OK;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return QSGD_ERR_HIP;
+  if (dev != L->device || p->d != L->d || p->n < L->extent) return QSGD_ERR_INVALID_ARG;
+  g.d = L->d;
+  g.nb = L->nb;
+  g.table_words = p->code == QSGD_CODE_FIXED ? 0 : ((g.nb + 1 + 3) & ~(uint64_t)3);
+  return QSGD_OK;
+}
+
+// Worst-case words of all bucket strings of a tensor-aware message.
+uint64_t layout_string_words(const Geometry& g, const qsgd_layout* L) {
+  if (g.code == QSGD_CODE_FIXED) return g.nb * g.max_words(g.d);   // one full slot per bucket
+  uint64_t w = (g.nb - L->short_buckets) * g.max_words(g.d);
+  for (uint32_t m : L->short_len) w += g.max_words(m);
+  return w;
+}
+
+RawArgs raw_args(const Geometry& g, const qsgd_layout* L) {
+  RawArgs r;
+  std::memset(&r, 0, sizeof r);
+  r.rtab = L->rtab; r.R = L->R; r.raw_words = L->raw;
+  r.fixed_strings = g.code == QSGD_CODE_FIXED ? g.nb * g.max_words(g.d) : 0;
+  r.nb = (uint32_t)g.nb;
+  return r;
+}
+
+int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* msgs_dev,
+               const size_t* msg_bytes, uint32_t K, float c, uint32_t step, float* x_dev,
+               void* ws, size_t ws_bytes, void* hip_stream) {
+  Geometry g;
+  int rc = layout_geometry(p, L, g);
+  if (rc) return rc;
+  if (L && !g.bucket_path()) return QSGD_ERR_UNSUPPORTED;
   if (!msgs_dev || !msg_bytes || K < 1 || K > QSGD_MAX_PEERS || !ws || !aligned16(ws))
     return QSGD_ERR_INVALID_ARG;
   if (g.n > 0 && (!x_dev || !aligned16(x_dev))) return QSGD_ERR_INVALID_ARG;
-  if (ws_bytes < qsgd_workspace_bytes(p, K)) return QSGD_ERR_CAPACITY;
+  if (ws_bytes < (L ? qsgd_layout_workspace_bytes(p, L, K) : qsgd_workspace_bytes(p, K)))
+    return QSGD_ERR_CAPACITY;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
 
   DecodeArgs a;
@@ -200,6 +252,8 @@ int run_decode(const qsgd_params* p, const void* const* msgs_dev, const size_t* 
   }
   a.K = K; a.n = g.n; a.d = (uint32_t)g.d; a.nb = (uint32_t)g.nb; a.s = g.s; a.code = g.code;
   a.norm_mode = g.norm; a.table_words = (uint32_t)g.table_words;
+  a.btab = L ? L->btab : nullptr;
+  a.version = L ? 2 : 1;
   a.x = x_dev; a.c = c; a.step = step;
   a.status = static_cast<uint32_t*>(ws);
   a.fixed_bits = g.fixed_bits;
@@ -211,6 +265,11 @@ int run_decode(const qsgd_params* p, const void* const* msgs_dev, const size_t* 
   }
   if (g.n == 0) return QSGD_OK;
   const uint32_t cus = (uint32_t)device_cus();
+  if (L && L->R) {   // the small tensors: raw values behind the strings
+    ScopedTiming tm("decode_raw", st);
+    if (launch_raw_apply(a, raw_args(g, L), st) != hipSuccess) return QSGD_ERR_HIP;
+  }
+  if (g.nb == 0) return QSGD_OK;
   if (!g.bucket_path()) {
     const uint32_t blocks = (uint32_t)std::min<uint64_t>((g.n + 255) / 256, (uint64_t)cus * 32);
     ScopedTiming tm("decode_general", st);
@@ -294,11 +353,14 @@ size_t qsgd_workspace_bytes(const qsgd_params* p, uint32_t K) {
   return (size_t)((bytes + 255) & ~(uint64_t)255);
 }
 
-int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t msg_capacity,
-                void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+static int encode_impl(const qsgd_params* p, const qsgd_layout* L, const float* g_dev,
+                       void* msg_dev, size_t msg_capacity, void* workspace_dev,
+                       size_t workspace_bytes, void* hip_stream) {
   Geometry g;
-  int rc = make_geometry(p, g);
+  int rc = layout_geometry(p, L, g);
   if (rc) return rc;
+  if (L && !g.bucket_path()) return QSGD_ERR_UNSUPPORTED;
+  const uint64_t raw_words = L ? L->raw : 0;
   if (!msg_dev || !aligned16(msg_dev) || !workspace_dev || !aligned16(workspace_dev))
     return QSGD_ERR_INVALID_ARG;
   if (g.n > 0 && (!g_dev || !aligned16(g_dev))) return QSGD_ERR_INVALID_ARG;
@@ -310,7 +372,7 @@ int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t 
   uint32_t* payload = header + H_WORDS + g.table_words;
   const uint64_t cap_words = (msg_capacity - fixed_part) / 4;
 
-  if (g.n == 0) {
+  if (g.n == 0 && !L) {
     ScopedTiming tm("encode_empty", st);
     if (launch_write_empty(header, table, g.code, g.norm, g.s, g.d, p->stream_id, p->iteration,
                            st) != hipSuccess)
@@ -357,19 +419,38 @@ int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t 
     return QSGD_OK;
   }
 
+  if (L && g.nb == 0) {   // every tensor travels raw: header (and an empty table) only
+    if (cap_words < raw_words) return QSGD_ERR_CAPACITY;
+    RawArgs ra = raw_args(g, L);
+    ra.g = g_dev; ra.header = header; ra.table = table; ra.payload = payload;
+    ra.cap_words = cap_words;
+    ScopedTiming tm("encode_raw", st);
+    if (launch_write_layout_header(header, table, g.code, g.norm, g.s, g.d, g.n, raw_words,
+                                   p->stream_id, p->iteration, st) != hipSuccess)
+      return QSGD_ERR_HIP;
+    if (launch_raw_pack(ra, st) != hipSuccess) return QSGD_ERR_HIP;
+    return QSGD_OK;
+  }
+
   EncodePlan pl;
   int tw, cpw;
   team_shape(g.d, tw, cpw);
   const uint32_t target = std::min<uint32_t>(kMaxTeams, (uint32_t)device_cus() * (32u / tw));
   plan_encode(g, target, pl);
   if (workspace_bytes < kStatusBytes + pl.ws_bytes) return QSGD_ERR_CAPACITY;
-  if (g.code == QSGD_CODE_FIXED && cap_words < g.max_payload_words()) return QSGD_ERR_CAPACITY;
+  // fixed width: the size of the message does not depend on the data
+  const uint64_t fixed_words =
+      g.code != QSGD_CODE_FIXED ? 0
+      : (L ? layout_string_words(g, L) : g.max_payload_words()) + raw_words;
+  if (g.code == QSGD_CODE_FIXED && cap_words < fixed_words) return QSGD_ERR_CAPACITY;
 
   uint8_t* wsb = static_cast<uint8_t*>(workspace_dev) + kStatusBytes;
   EncodeArgs a;
   std::memset(&a, 0, sizeof a);
   a.g = g_dev; a.n = g.n; a.d = (uint32_t)g.d; a.nb = (uint32_t)g.nb; a.s = g.s;
   a.norm_mode = g.norm;
+  a.btab = L ? L->btab : nullptr;
+  a.version = L ? 2 : 1;
   a.key0 = (uint32_t)p->seed; a.key1 = (uint32_t)(p->seed >> 32);
   a.stream_id = p->stream_id; a.iteration = p->iteration;
   a.bper = pl.bper; a.dst_words = pl.dst_words; a.sub_words = pl.sub_words;
@@ -380,7 +461,13 @@ int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t 
   a.payload = payload;
   a.fixed_bits = g.fixed_bits;
   a.fixed_words_full = (uint32_t)g.max_words(g.d);
-  a.fixed_payload_words = g.code == QSGD_CODE_FIXED ? g.max_payload_words() : 0;
+  a.fixed_payload_words = fixed_words;
+  RawArgs ra;
+  if (L) {
+    ra = raw_args(g, L);
+    ra.g = g_dev; ra.header = header; ra.table = table; ra.payload = payload;
+    ra.cap_words = cap_words;
+  }
   if (g.code == QSGD_CODE_FIXED && g.d <= 1024) {
     // small buckets: several ride in one wavefront
     const int lpb = g.d <= 256 ? 16 : g.d <= 512 ? 32 : 64;
@@ -391,8 +478,14 @@ int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t 
     const uint32_t t = std::max(1u, std::min(groups, want));
     a.bper = (groups + t - 1) / t;
     const uint32_t teams = (groups + a.bper - 1) / a.bper;
-    ScopedTiming tm("encode_bucket", st);
-    if (launch_encode_fixed_small(a, lpb, cp, teams, st) != hipSuccess) return QSGD_ERR_HIP;
+    {
+      ScopedTiming tm("encode_bucket", st);
+      if (launch_encode_fixed_small(a, lpb, cp, teams, st) != hipSuccess) return QSGD_ERR_HIP;
+    }
+    if (L && L->R) {
+      ScopedTiming tm("encode_raw", st);
+      if (launch_raw_pack(ra, st) != hipSuccess) return QSGD_ERR_HIP;
+    }
     return QSGD_OK;
   }
   {
@@ -405,17 +498,38 @@ int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t 
     c.staging = a.staging; c.region_words = pl.region_words; c.totals = a.totals;
     c.table = table; c.payload = payload; c.header = header; c.cap_words = cap_words;
     c.bper = pl.bper; c.nb = (uint32_t)g.nb; c.table_words = (uint32_t)g.table_words;
+    c.raw_words = raw_words;
     ScopedTiming tm("encode_compact", st);
     if (launch_encode_compact(c, pl.teams, st) != hipSuccess) return QSGD_ERR_HIP;
+  }
+  if (L && L->R) {
+    ScopedTiming tm("encode_raw", st);
+    if (launch_raw_pack(ra, st) != hipSuccess) return QSGD_ERR_HIP;
   }
   return QSGD_OK;
 }
 
+int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t msg_capacity,
+                void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  return encode_impl(p, nullptr, g_dev, msg_dev, msg_capacity, workspace_dev, workspace_bytes,
+                     hip_stream);
+}
+
+int qsgd_encode_layout(const qsgd_params* p, const qsgd_layout* layout, const float* g_dev,
+                       void* msg_dev, size_t msg_capacity, void* workspace_dev,
+                       size_t workspace_bytes, void* hip_stream) {
+  if (!layout) return QSGD_ERR_INVALID_ARG;
+  return encode_impl(p, layout, g_dev, msg_dev, msg_capacity, workspace_dev, workspace_bytes,
+                     hip_stream);
+}
+
+
+
 int qsgd_decode_accumulate(const qsgd_params* p, const void* const* msgs_dev,
                            const size_t* msg_bytes, uint32_t K, float* acc_dev,
                            void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
-  return run_decode(p, msgs_dev, msg_bytes, K, 0.f, 0, acc_dev, workspace_dev, workspace_bytes,
-                    hip_stream);
+  return run_decode(p, nullptr, msgs_dev, msg_bytes, K, 0.f, 0, acc_dev, workspace_dev,
+                    workspace_bytes, hip_stream);
 }
 
 int qsgd_sgd_step(const qsgd_params* p, const void* const* msgs_dev, const size_t* msg_bytes,
@@ -423,15 +537,112 @@ int qsgd_sgd_step(const qsgd_params* p, const void* const* msgs_dev, const size_
                   size_t workspace_bytes, void* hip_stream) {
   if (K < 1) return QSGD_ERR_INVALID_ARG;
   const float c = eta / (float)K;
-  return run_decode(p, msgs_dev, msg_bytes, K, c, 1, x_dev, workspace_dev, workspace_bytes,
-                    hip_stream);
+  return run_decode(p, nullptr, msgs_dev, msg_bytes, K, c, 1, x_dev, workspace_dev,
+                    workspace_bytes, hip_stream);
+}
+
+int qsgd_decode_accumulate_layout(const qsgd_params* p, const qsgd_layout* layout,
+                                  const void* const* msgs_dev, const size_t* msg_bytes,
+                                  uint32_t K, float* acc_dev, void* workspace_dev,
+                                  size_t workspace_bytes, void* hip_stream) {
+  if (!layout) return QSGD_ERR_INVALID_ARG;
+  return run_decode(p, layout, msgs_dev, msg_bytes, K, 0.f, 0, acc_dev, workspace_dev,
+                    workspace_bytes, hip_stream);
+}
+
+int qsgd_sgd_step_layout(const qsgd_params* p, const qsgd_layout* layout,
+                         const void* const* msgs_dev, const size_t* msg_bytes, uint32_t K,
+                         float eta, float* x_dev, void* workspace_dev, size_t workspace_bytes,
+                         void* hip_stream) {
+  if (!layout || K < 1) return QSGD_ERR_INVALID_ARG;
+  return run_decode(p, layout, msgs_dev, msg_bytes, K, eta / (float)K, 1, x_dev, workspace_dev,
+                    workspace_bytes, hip_stream);
+}
+
+int qsgd_layout_create(const uint64_t* offsets, const uint64_t* sizes, uint32_t T, uint64_t d,
+                       uint64_t bypass_below, qsgd_layout** out) {
+  if (!out || (T && (!offsets || !sizes)) || d < 4 || d % 4 || d > kMaxBucketFast)
+    return d > kMaxBucketFast || (d % 4) ? QSGD_ERR_UNSUPPORTED : QSGD_ERR_INVALID_ARG;
+  std::vector<uint2> bt;
+  std::vector<uint4> rt;
+  qsgd_layout* L = new (std::nothrow) qsgd_layout;
+  if (!L) return QSGD_ERR_INVALID_ARG;
+  L->d = d; L->bypass = bypass_below;
+  uint64_t prev_end = 0;
+  for (uint32_t j = 0; j < T; ++j) {   // ascending, disjoint, 16-byte aligned starts
+    const uint64_t off = offsets[j], sz = sizes[j];
+    if (off < prev_end || (off % 4) || off + sz > 0xFFFFFFFFull) { delete L; return QSGD_ERR_INVALID_ARG; }
+    prev_end = off + sz;
+    if (sz < bypass_below) {
+      if (sz) rt.push_back(make_uint4((uint32_t)(off / 4), (uint32_t)sz, (uint32_t)L->raw, 0));
+      L->raw += sz;
+      continue;
+    }
+    for (uint64_t o = 0; o < sz; o += d) {
+      const uint32_t m = (uint32_t)std::min<uint64_t>(d, sz - o);
+      bt.push_back(make_uint2((uint32_t)((off + o) / 4), m));
+      if (m < d) { L->short_buckets++; L->short_values += m; L->short_len.push_back(m); }
+    }
+  }
+  L->extent = prev_end;
+  L->nb = bt.size();
+  L->R = (uint32_t)rt.size();
+  if (L->nb > 0x7FFFFFFFull || L->raw > 0xFFFFFFFFull) { delete L; return QSGD_ERR_UNSUPPORTED; }
+  bool ok = hipGetDevice(&L->device) == hipSuccess;
+  if (ok && !bt.empty()) {
+    ok = hipMalloc(reinterpret_cast<void**>(&L->btab), bt.size() * sizeof(uint2)) == hipSuccess &&
+         hipMemcpy(L->btab, bt.data(), bt.size() * sizeof(uint2), hipMemcpyHostToDevice) == hipSuccess;
+  }
+  if (ok && !rt.empty()) {
+    ok = hipMalloc(reinterpret_cast<void**>(&L->rtab), rt.size() * sizeof(uint4)) == hipSuccess &&
+         hipMemcpy(L->rtab, rt.data(), rt.size() * sizeof(uint4), hipMemcpyHostToDevice) == hipSuccess;
+  }
+  if (!ok) { qsgd_layout_destroy(L); return QSGD_ERR_HIP; }
+  *out = L;
+  return QSGD_OK;
+}
+
+void qsgd_layout_destroy(qsgd_layout* layout) {
+  if (!layout) return;
+  if (layout->btab) (void)hipFree(layout->btab);
+  if (layout->rtab) (void)hipFree(layout->rtab);
+  delete layout;
+}
+
+int qsgd_layout_info(const qsgd_layout* layout, uint64_t* buckets, uint64_t* raw_values,
+                     uint64_t* extent) {
+  if (!layout) return QSGD_ERR_INVALID_ARG;
+  if (buckets) *buckets = layout->nb;
+  if (raw_values) *raw_values = layout->raw;
+  if (extent) *extent = layout->extent;
+  return QSGD_OK;
+}
+
+size_t qsgd_layout_max_encoded_bytes(const qsgd_params* p, const qsgd_layout* layout) {
+  Geometry g;
+  if (!layout || make_geometry(p, g) || p->d != layout->d || p->n < layout->extent) return 0;
+  g.d = layout->d; g.nb = layout->nb;
+  g.table_words = p->code == QSGD_CODE_FIXED ? 0 : ((g.nb + 1 + 3) & ~(uint64_t)3);
+  return (size_t)(4 * (H_WORDS + g.table_words + layout_string_words(g, layout) + layout->raw));
+}
+
+size_t qsgd_layout_workspace_bytes(const qsgd_params* p, const qsgd_layout* layout, uint32_t K) {
+  Geometry g;
+  if (!layout || make_geometry(p, g) || K > QSGD_MAX_PEERS || p->d != layout->d) return 0;
+  g.d = layout->d; g.nb = layout->nb;
+  uint64_t bytes = kStatusBytes + kTotalsBytes;
+  if (g.code != QSGD_CODE_FIXED) {
+    const uint64_t slots = g.nb + std::min<uint64_t>(g.nb, kMaxTeams);
+    bytes += slots * (g.max_words(g.d) + 4) * 4;
+  }
+  return (size_t)((bytes + 255) & ~(uint64_t)255);
 }
 
 int qsgd_message_info(const void* header_host, qsgd_params* out, uint64_t* total_bytes) {
   if (!header_host) return QSGD_ERR_INVALID_ARG;
   uint32_t h[H_WORDS];
   std::memcpy(h, header_host, sizeof h);
-  if (h[H_MAGIC] != kMagic || h[H_VERSION] != 1) return QSGD_ERR_CORRUPT;
+  if (h[H_MAGIC] != kMagic || (h[H_VERSION] != 1 && h[H_VERSION] != 2)) return QSGD_ERR_CORRUPT;
   qsgd_params q;
   std::memset(&q, 0, sizeof q);
   q.code = h[H_CODE]; q.norm = h[H_NORM]; q.s = h[H_S];
@@ -441,6 +652,10 @@ int qsgd_message_info(const void* header_host, qsgd_params* out, uint64_t* total
   Geometry g;
   if (make_geometry(&q, g)) return QSGD_ERR_CORRUPT;
   const uint64_t pw = h[H_PW_LO] | ((uint64_t)h[H_PW_HI] << 32);
+  if (h[H_VERSION] == 2) {   // tensor-aware: the bucket count is the layout's, not ceil(n / d)
+    const uint64_t nb = h[H_NB_LO] | ((uint64_t)h[H_NB_HI] << 32);
+    g.table_words = q.code == QSGD_CODE_FIXED ? 0 : ((nb + 1 + 3) & ~(uint64_t)3);
+  }
   if (out) *out = q;
   if (total_bytes) *total_bytes = 4 * (H_WORDS + g.table_words + pw);
   const int status = (int)h[H_STATUS];

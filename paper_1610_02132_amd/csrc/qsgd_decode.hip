@@ -71,7 +71,7 @@ __global__ void k_decode_check(DecodeArgs a) {
   if (ok) {
     const uint32_t* h = a.msgs[k];
     const uint64_t pw = h[H_PW_LO] | ((uint64_t)h[H_PW_HI] << 32);
-    ok = h[H_MAGIC] == kMagic && h[H_VERSION] == 1 && h[H_CODE] == a.code &&
+    ok = h[H_MAGIC] == kMagic && h[H_VERSION] == a.version && h[H_CODE] == a.code &&
          h[H_NORM] == a.norm_mode && h[H_S] == a.s && h[H_D_LO] == a.d && h[H_D_HI] == 0 &&
          h[H_N_LO] == (uint32_t)a.n && h[H_N_HI] == (uint32_t)(a.n >> 32) &&
          h[H_NB_LO] == a.nb && h[H_NB_HI] == 0 && h[H_STATUS] == 0 &&
@@ -103,8 +103,9 @@ __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
   const uint64_t all_ok = K >= 64 ? ~0ull : ((1ull << K) - 1ull);
 
   for (uint32_t b = wave_global; b < a.nb; b += wave_count) {
-    const uint64_t base = (uint64_t)b * a.d;
-    const uint32_t m = (uint32_t)min((uint64_t)a.d, a.n - base);
+    uint64_t base;
+    uint32_t m;
+    bucket_extent(a, b, base, m);
     const uint32_t lw = (m * B + 31u) >> 5, sw = (m + 31u) >> 5;
     const uint64_t str_off = (uint64_t)H_WORDS + (uint64_t)b * a.fixed_words_full;
     float my_scale = 0.f;
@@ -282,7 +283,8 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   bool open = false;
   float my_scale = 0.f;
   if (g < gcount) {
-    m = (uint32_t)min((uint64_t)a.d, a.n - (uint64_t)b * a.d);
+    uint64_t base_unused;
+    bucket_extent(a, b, base_unused, m);
     const uint32_t* msg = a.msgs[k];
     const uint32_t o0 = msg[H_WORDS + b], o1 = msg[H_WORDS + b + 1];
     if (o0 < o1 && pay + o1 <= a.msg_words[k]) {
@@ -406,8 +408,9 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     for (int qi = 0; qi < NQ; ++qi) {
       dst[qi] = make_float4(0.f, 0.f, 0.f, 0.f);
       if ((uint32_t)qi < gcount) {
-        const uint64_t base = (uint64_t)(b0 + qi) * a.d;
-        const uint32_t mb = (uint32_t)min((uint64_t)a.d, a.n - base);
+        uint64_t base;
+        uint32_t mb;
+        bucket_extent(a, b0 + (uint32_t)qi, base, mb);
         const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
         const float* xp = a.x + base + ws + i;
         if (i + 3 < cntw) {
@@ -586,8 +589,9 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
       if ((uint32_t)qi < gcount) {
-        const uint64_t base = (uint64_t)(b0 + qi) * a.d;
-        const uint32_t mb = (uint32_t)min((uint64_t)a.d, a.n - base);
+        uint64_t base;
+        uint32_t mb;
+        bucket_extent(a, b0 + (uint32_t)qi, base, mb);
         const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
         float* xp = a.x + base + ws + i;
         float* ap = acc + qi * winp + i;

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
 
   if (blockIdx.x == 0 && tid == 0) {  // header; length and status are completed later
     uint32_t* h = a.header;
-    h[H_MAGIC] = kMagic; h[H_VERSION] = 1; h[H_CODE] = CODE; h[H_NORM] = a.norm_mode;
+    h[H_MAGIC] = kMagic; h[H_VERSION] = a.version; h[H_CODE] = CODE; h[H_NORM] = a.norm_mode;
     h[H_S] = a.s; h[H_STREAM] = a.stream_id;
     h[H_D_LO] = (uint32_t)a.d; h[H_D_HI] = 0;
     h[H_N_LO] = (uint32_t)a.n; h[H_N_HI] = (uint32_t)(a.n >> 32);
@@ -78,8 +78,9 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
   const float s_f = (float)s;
 
   for (uint32_t b = b_begin; b < b_end; ++b) {
-    const uint64_t base = (uint64_t)b * a.d;
-    const uint32_t m = (uint32_t)min((uint64_t)a.d, a.n - base);
+    uint64_t base;
+    uint32_t m;
+    bucket_extent(a, b, base, m);
     const float* __restrict__ gb = a.g + base;
 
     // ---- read the bucket once, accumulate the scale --------------------------
@@ -191,6 +192,11 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
         const uint32_t si = e0 >> 5;
         if ((lane & 7) == 0 && si < sw) splane[si] = sg;
       }
+      // a short bucket inside a tensor-aware message keeps a full-size slot: zero its tail
+      if (a.btab && m < a.d) {
+        for (uint32_t w = 2u + lw + sw + (uint32_t)tid; w < a.fixed_words_full; w += 64 * TW)
+          str[w] = 0;
+      }
       // escape word: at most one lane of the team holds an index
       const uint64_t eb = __ballot(esc != 0xFFFFFFFFu);
       if (TW == 1) {
@@ -295,7 +301,7 @@ __global__ __launch_bounds__(64) void k_encode_fixed_small(EncodeArgs a) {
 
   if (blockIdx.x == 0 && lane == 0) {
     uint32_t* h = a.header;
-    h[H_MAGIC] = kMagic; h[H_VERSION] = 1; h[H_CODE] = QSGD_CODE_FIXED; h[H_NORM] = a.norm_mode;
+    h[H_MAGIC] = kMagic; h[H_VERSION] = a.version; h[H_CODE] = QSGD_CODE_FIXED; h[H_NORM] = a.norm_mode;
     h[H_S] = a.s; h[H_STREAM] = a.stream_id;
     h[H_D_LO] = (uint32_t)a.d; h[H_D_HI] = 0;
     h[H_N_LO] = (uint32_t)a.n; h[H_N_HI] = (uint32_t)(a.n >> 32);
@@ -315,8 +321,9 @@ __global__ __launch_bounds__(64) void k_encode_fixed_small(EncodeArgs a) {
   for (uint32_t grp = g_begin; grp < g_end; ++grp) {
     const uint32_t b = grp * NB + sb;
     const bool live = b < a.nb;
-    const uint64_t base = (uint64_t)b * a.d;
-    const uint32_t m = live ? (uint32_t)min((uint64_t)a.d, a.n - base) : 0u;
+    uint64_t base = 0;
+    uint32_t m = 0;
+    if (live) bucket_extent(a, b, base, m);
     const float* __restrict__ gb = a.g + base;
     // every lane's CP quads lie inside its bucket: no per-element bounds needed
     const bool all_full = __ballot(m == (uint32_t)CP * kStep) == ~0ull;
@@ -426,6 +433,10 @@ __global__ __launch_bounds__(64) void k_encode_fixed_small(EncodeArgs a) {
       const uint32_t si = e0 >> 5;
       if ((l & 7) == 0 && (all_full || si < sw)) splane[si] = sg;
     }
+    // a short bucket inside a tensor-aware message keeps a full-size slot: zero its tail
+    if (a.btab && live && m < a.d) {
+      for (uint32_t w = 2u + lw + sw + l; w < a.fixed_words_full; w += LPB) str[w] = 0;
+    }
     // escape word of each bucket: at most one of its lanes holds an index
     const uint64_t eb = __ballot(esc != 0xFFFFFFFFu);
     if (eb) {
@@ -472,8 +483,10 @@ __global__ __launch_bounds__(256) void k_encode_compact(CompactArgs a) {
       const uint64_t total = base + mine;
       a.table[a.nb] = (uint32_t)min(total, (uint64_t)0xFFFFFFFFull);
       for (uint32_t i = a.nb + 1; i < a.table_words; ++i) a.table[i] = 0;  // padding
-      a.header[H_PW_LO] = (uint32_t)total;
-      a.header[H_PW_HI] = (uint32_t)(total >> 32);
+      const uint64_t all = total + a.raw_words;   // the raw values follow the strings
+      if (all > a.cap_words) atomicExch(&a.header[H_STATUS], (uint32_t)QSGD_ERR_CAPACITY);
+      a.header[H_PW_LO] = (uint32_t)all;
+      a.header[H_PW_HI] = (uint32_t)(all >> 32);
     }
   }
 }

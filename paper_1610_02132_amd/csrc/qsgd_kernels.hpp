@@ -42,8 +42,25 @@ constexpr uint32_t kParse = QSGD_PARSE;      // Elias decode: trips of a short p
 constexpr uint32_t kParseLanes = QSGD_PARSE_LANES;  // lanes with room that start a pass
 constexpr uint32_t kStrFetch = kStrWin / 2; // words fetched at a time
 
+// Tensor-aware messages: bucket b covers values [4 * btab[b].x, 4 * btab[b].x + btab[b].y)
+// of the arena (a null table means bucket b = [b*d, min(n, (b+1)*d))).
+template <class Args>
+__device__ __forceinline__ void bucket_extent(const Args& a, uint32_t b, uint64_t& base,
+                                              uint32_t& m) {
+  if (a.btab) {
+    const uint2 e = a.btab[b];
+    base = (uint64_t)e.x * 4u;
+    m = e.y;
+  } else {
+    base = (uint64_t)b * a.d;
+    m = (uint32_t)min((uint64_t)a.d, a.n - base);
+  }
+}
+
 struct EncodeArgs {
   const float* g;
+  const uint2* btab;    // per-bucket (start / 4, length) or null
+  uint32_t version;     // header version: 1 flat, 2 tensor-aware
   uint64_t n;
   uint32_t d;           // bucket size (<= kMaxBucketFast on this path)
   uint32_t nb;          // number of buckets
@@ -77,12 +94,15 @@ struct CompactArgs {
   uint32_t bper;
   uint32_t nb;
   uint32_t table_words;  // padded table length
+  uint64_t raw_words;    // raw fp32 words that follow the strings (tensor-aware messages)
 };
 
 struct DecodeArgs {
   const uint32_t* msgs[QSGD_MAX_PEERS];
   uint64_t msg_words[QSGD_MAX_PEERS];  // readable words behind each pointer
   uint32_t K;
+  const uint2* btab;     // per-bucket (start / 4, length) or null
+  uint32_t version;      // header version the messages must carry
   uint64_t n;
   uint32_t d;
   uint32_t nb;
@@ -102,6 +122,21 @@ struct DecodeArgs {
   // fixed width
   uint32_t fixed_bits;
   uint32_t fixed_words_full;
+};
+
+// Raw section of tensor-aware messages: tensor r of the small ones.
+struct RawArgs {
+  const uint4* rtab;         // (start / 4, length, offset in the raw section, 0)
+  uint32_t R;
+  uint64_t raw_words;        // all raw values of a message
+  uint64_t fixed_strings;    // fixed width: words of all bucket strings; else 0 (read the table)
+  // encode
+  const float* g;
+  uint32_t* header;
+  const uint32_t* table;
+  uint32_t* payload;
+  uint64_t cap_words;
+  uint32_t nb;
 };
 
 constexpr uint32_t kSeg = 2048;  // values per segment on the general path
@@ -145,6 +180,12 @@ hipError_t launch_decode_check(const DecodeArgs& a, hipStream_t st);
 hipError_t launch_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t st);
 hipError_t launch_decode_elias(const DecodeArgs& a, uint32_t blocks, size_t lds, hipStream_t st);
 
+hipError_t launch_write_layout_header(uint32_t* header, uint32_t* table, uint32_t code,
+                                      uint32_t norm, uint32_t s, uint64_t d, uint64_t n,
+                                      uint64_t raw_words, uint32_t stream_id, uint32_t iteration,
+                                      hipStream_t st);
+hipError_t launch_raw_pack(const RawArgs& a, hipStream_t st);
+hipError_t launch_raw_apply(const DecodeArgs& a, const RawArgs& r, hipStream_t st);
 hipError_t launch_gen_partial(const GenArgs& a, hipStream_t st);
 hipError_t launch_gen_scale(const GenArgs& a, hipStream_t st);
 hipError_t launch_gen_encode(const GenArgs& a, bool aligned, hipStream_t st);

@@ -1,0 +1,135 @@
+"""GPU parity of the tensor-aware messages (small tensors raw, buckets restart at every
+tensor) against the oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_1610_02132_amd as q  # noqa: E402
+from oracle import qsgd_oracle as qo  # noqa: E402
+from paper_1610_02132_amd import workloads as W  # noqa: E402
+
+
+def arena_of(sizes, align=4):
+    tensors, off = [], 0
+    for sz in sizes:
+        tensors.append((off, int(sz)))
+        off += (int(sz) + align - 1) // align * align
+    return tensors, off
+
+
+def gradient(n, seed, scale=1e-2):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    return torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, scale, generator=g)
+
+
+def encode_gpu(P, L, g, cap=None):
+    cap = q.qsgd_layout_max_encoded_bytes(P, L) if cap is None else cap
+    ws = torch.zeros(max(q.qsgd_layout_workspace_bytes(P, L, 1), 256) // 4, dtype=torch.int32,
+                     device="cuda")
+    msg = torch.full((cap // 4 + 4,), -1, dtype=torch.int32, device="cuda")
+    q.qsgd_encode_layout(P, L, g, msg[: cap // 4], ws)
+    status, total = q.qsgd_message_status(msg)
+    host = msg.cpu().numpy().view(np.uint32)
+    assert np.all(host[cap // 4:] == 0xFFFFFFFF), "write past the message capacity"
+    return status, total, host, msg
+
+
+def check_messages(P, tensors, bypass, g_host, gpu_words):
+    Po = qo.Params(n=P.n, s=P.s, d=P.d, code=P.code, norm=P.norm, seed=P.seed,
+                   stream_id=P.stream_id, iteration=P.iteration)
+    ref = qo.encode_layout(Po, tensors, bypass, g_host)
+    if ref.size == gpu_words.size and np.array_equal(ref, gpu_words):
+        return
+    # not byte-identical: only near-tie elements may differ, at most 1e-6 of them
+    a = qo.decode_layout(tensors, bypass, gpu_words, P.n)
+    b = qo.decode_layout(tensors, bypass, ref, P.n)
+    diff = int(np.count_nonzero(a.view(np.uint32) != b.view(np.uint32)))
+    assert diff <= max(1, int(1e-6 * P.n)), f"{diff} decoded values differ"
+
+
+CASES = [
+    # name, tensor sizes, d, s, code, norm, bypass
+    ("c2_like_sparse", [max(1, t // 16) for t in W.C2.tensors], 512, 16, q.CODE_SPARSE, q.NORM_L2, 10_000),
+    ("c3_like_fixed", [max(1, t // 64) for t in W.C3.tensors], 512, 256, q.CODE_FIXED, q.NORM_L2, 10_000),
+    ("dense_code", [37, 1300, 9, 512, 2050, 700, 40_000], 256, 7, q.CODE_DENSE, q.NORM_L2, 600),
+    ("max_norm_fixed", [5, 3000, 20_000, 11, 4097], 1024, 15, q.CODE_FIXED, q.NORM_MAX, 100),
+    ("big_buckets_sparse", [100_000, 3, 50_001, 8192, 20_000], 8192, 4, q.CODE_SPARSE, q.NORM_L2, 10),
+    ("wide_fixed", [100_000, 3, 50_001, 4096], 4096, 4, q.CODE_FIXED, q.NORM_L2, 10),
+    ("all_raw", [100, 7, 2000], 512, 4, q.CODE_SPARSE, q.NORM_L2, 10_000),
+    ("all_quantized", [5000, 777, 12_345], 512, 4, q.CODE_SPARSE, q.NORM_L2, 0),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_layout_encode_and_step_match_oracle(case):
+    name, sizes, d, s, code, norm, bypass = case
+    tensors, n = arena_of(sizes)
+    K, eta = 3, 0.1
+    L = q.Layout(tensors, d, bypass)
+    nb, raw, extent = q.qsgd_layout_info(L)
+    nbo, rawo = qo.layout_counts(qo.Params(n=n, s=s, d=d, code=code, norm=norm), tensors, bypass)
+    assert (nb, raw) == (nbo, rawo) and extent <= n
+    msgs_dev, msgs_host, sizes_b = [], [], []
+    for k in range(K):
+        P = q.Params(n=n, s=s, d=d, code=code, norm=norm, seed=5, stream_id=k, iteration=2)
+        g = gradient(n, 100 + k)
+        status, total, host, dev = encode_gpu(P, L, g)
+        assert status == 0, status
+        words = host[: total // 4].copy()
+        check_messages(P, tensors, bypass, g.cpu().numpy(), words)
+        msgs_dev.append(dev)
+        msgs_host.append(words)
+        sizes_b.append(total)
+    P0 = q.Params(n=n, s=s, d=d, code=code, norm=norm, seed=5)
+    ws = torch.zeros(max(q.qsgd_layout_workspace_bytes(P0, L, K), 256) // 4, dtype=torch.int32,
+                     device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    x0 = torch.empty(n, dtype=torch.float32, device="cuda").uniform_(-1, 1, generator=gen)
+    x = x0.clone()
+    q.qsgd_sgd_step_layout(P0, L, msgs_dev, eta, x, ws, msg_bytes=sizes_b)
+    assert q.qsgd_workspace_status(ws) == 0
+    want = qo.sgd_step_layout(tensors, bypass, msgs_host, eta, x0.cpu().numpy())
+    got = x.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), \
+        f"{np.count_nonzero(got != want)} of {n} values differ"
+    acc = x0.clone()
+    q.qsgd_decode_accumulate_layout(P0, L, msgs_dev, acc, ws, msg_bytes=sizes_b)
+    assert q.qsgd_workspace_status(ws) == 0
+    want = qo.decode_accumulate_layout(tensors, bypass, msgs_host, x0.cpu().numpy())
+    assert np.array_equal(acc.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    L.close()
+
+
+def test_layout_argument_and_capacity_checks():
+    tensors, n = arena_of([4000, 50, 9000])
+    L = q.Layout(tensors, 512, 100)
+    P = q.Params(n=n, s=4, d=512)
+    g = gradient(n, 1)
+    status, total, host, _ = encode_gpu(P, L, g)
+    assert status == 0
+    # a buffer one word short: reported in the header status, nothing written past it
+    status2, need, _, _ = encode_gpu(P, L, g, cap=total - 4)
+    assert status2 == -2   # QSGD_ERR_CAPACITY
+    # flat decoders refuse a tensor-aware message and the other way round
+    ws = torch.zeros(max(q.qsgd_layout_workspace_bytes(P, L, 1), q.qsgd_workspace_bytes(P, 1)) // 4,
+                     dtype=torch.int32, device="cuda")
+    msg = torch.from_numpy(host[: total // 4].view(np.int32).copy()).cuda()
+    x = torch.zeros(n, dtype=torch.float32, device="cuda")
+    q.qsgd_sgd_step(P, [msg], 0.1, x, ws)
+    assert q.qsgd_workspace_status(ws) != 0 and not x.any()
+    # wrong d, arena too small, unaligned or overlapping tensors
+    with pytest.raises(q.QsgdError):
+        q.qsgd_encode_layout(q.Params(n=n, s=4, d=256), L, g, msg, ws)
+    with pytest.raises(q.QsgdError):
+        q.qsgd_encode_layout(q.Params(n=n - 8, s=4, d=512), L, g[: n - 8], msg, ws)
+    with pytest.raises(q.QsgdError):
+        q.Layout([(2, 100)], 512, 10)
+    with pytest.raises(q.QsgdError):
+        q.Layout([(0, 100), (64, 100)], 512, 10)
+    with pytest.raises(q.QsgdError):
+        q.Layout([(0, 100)], 510, 10)
+    L.close()
