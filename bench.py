@@ -63,6 +63,9 @@ def main() -> int:
                     help="tensor-aware messages: the workload's tensors in an arena, tensors "
                          "below --bypass elements sent raw, buckets restart at every tensor")
     ap.add_argument("--bypass", type=int, default=10_000)
+    ap.add_argument("--pipeline", type=int, default=0, metavar="CHUNK",
+                    help="double-buffered pass: chunks of CHUNK elements (a multiple of d), the "
+                         "encodes of one chunk overlapping decode+step of the previous one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="target CPU time of the oracle baseline sample")
@@ -140,6 +143,10 @@ def main() -> int:
         def step():
             q.qsgd_sgd_step(params(0), msgs, w.eta, x, ws)
 
+    if args.pipeline:
+        if args.layout or args.pipeline % min(w.d, n):
+            log("bench.py: --pipeline needs a flat workload and a chunk that is a multiple of d")
+            return 2
     ws = torch.empty(ws_bytes // 4, dtype=torch.int32, device="cuda")
     # size the message buffers from a first encode into a worst-case buffer
     probe = torch.empty(cap_max // 4, dtype=torch.int32, device="cuda")
@@ -156,16 +163,29 @@ def main() -> int:
             encode(k, msgs[k])
         step()
 
+    if args.pipeline:
+        chunk = min(args.pipeline, n)
+        pc = q.Params(n=chunk, s=w.s, d=w.d, code=w.code)
+        cap_c = min(q.qsgd_max_encoded_bytes(pc), (int(total0 * 1.3 * chunk / n) + 65536) & ~255)
+        del msgs
+        msgs = [torch.empty(cap_c // 4, dtype=torch.int32, device="cuda") for _ in range(2 * K)]
+        ws2 = torch.empty(ws_bytes // 4, dtype=torch.int32, device="cuda")
+        pipe = q.Pipeline()
+
+        def one_step():   # noqa: F811
+            q.qsgd_pipeline_step(pipe, params(0), chunk, grads, w.eta, x, msgs, ws, ws2)
+
     for _ in range(max(args.warmup, 1)):   # at least one untimed pass fills the messages
         one_step()
     torch.cuda.synchronize()
     sizes = []
-    for k in range(K):
+    for k in range(len(msgs)):
         st, tot = q.qsgd_message_status(msgs[k])
         assert st == 0, (k, st)
         sizes.append(tot)
-    assert q.qsgd_workspace_status(ws) == 0
-    msg_bytes_avg = float(np.mean(sizes))
+    assert q.qsgd_workspace_status(ws2 if args.pipeline else ws) == 0
+    # (pipelined: the buffers hold the last two chunks; scale to the whole vector)
+    msg_bytes_avg = float(total0) if args.pipeline else float(np.mean(sizes))
 
     # ---- timed region: exactly --steps steps ---------------------------------------
     q.qsgd_timing_reset()
@@ -177,7 +197,7 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     q.qsgd_timing_enable(False)
-    assert q.qsgd_workspace_status(ws) == 0
+    assert q.qsgd_workspace_status(ws2 if args.pipeline else ws) == 0
 
     ms_per_step = 1e3 * elapsed / args.steps
     n_arena, n = n, n_values      # throughput counts the values that belong to a tensor
@@ -200,6 +220,10 @@ def main() -> int:
     table_bytes = 0 if w.code == W.CODE_FIXED else 4 * (nb + 1)
     enc_alg = 4.0 * n + msg_bytes_avg                       # read g once, write the message once
     dec_alg = K * msg_bytes_avg + 8.0 * n                   # read K messages, read + write x
+    if args.pipeline:   # a launch covers one chunk (kernels of the two streams overlap in time)
+        nchunks = (n + args.pipeline - 1) // args.pipeline
+        enc_alg /= nchunks
+        dec_alg /= nchunks
     enc_main = "encode_bucket" if "encode_bucket" in kern else "encode_general"
     dec_main = next((k_ for k_ in ("decode_elias", "decode_fixed", "decode_general") if k_ in kern), None)
     enc_total = kern[enc_main]["ms_total"]
@@ -209,7 +233,7 @@ def main() -> int:
     else:
         dom, dom_alg = dec_main, dec_alg
     achieved = dom_alg / (kern[dom]["ms_avg"] * 1e-3) / 1e9
-    traffic = {} if args.layout else hbm_traffic(w.name, n)
+    traffic = {} if (args.layout or args.pipeline) else hbm_traffic(w.name, n)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": traffic.get(dom), "bytes_per_launch": dom_alg,
@@ -297,7 +321,9 @@ def main() -> int:
         "config": {"workload": f"{w.name}: n={n}, s={w.s}, d={w.d}, "
                                f"code={['sparse Elias', 'dense Elias', 'fixed width'][w.code]}, K={K}"
                                + (f", tensor-aware ({len(tensors)} tensors, raw below {args.bypass})"
-                                  if args.layout else ""),
+                                  if args.layout else "")
+                               + (f", double-buffered in chunks of {args.pipeline}"
+                                  if args.pipeline else ""),
                    "n": n, "s": w.s, "d": w.d, "K": K, "eta": w.eta,
                    "bits_per_element": round(8 * msg_bytes_avg / n, 4),
                    "message_bytes": int(msg_bytes_avg)},

@@ -171,6 +171,39 @@ int qsgd_sgd_step_layout(const qsgd_params *p, const qsgd_layout *layout,
                          float eta, float *x_dev, void *workspace_dev, size_t workspace_bytes,
                          void *hip_stream);
 
+/* Encode of a SLICE of a longer vector: as qsgd_encode on the p->n values at g_dev,
+ * with the rounding draws of positions index_base .. index_base + p->n - 1 of the
+ * whole vector (index_base a multiple of 4; bucket sizes as accepted by the bucket
+ * kernels: a multiple of 4, at most 8192, else QSGD_ERR_UNSUPPORTED when index_base
+ * is not 0).  If index_base is a multiple of the bucket size, the buckets and levels
+ * are exactly those the whole vector would get. */
+int qsgd_encode_slice(const qsgd_params *p, uint64_t index_base, const float *g_dev,
+                      void *msg_dev, size_t msg_capacity, void *workspace_dev,
+                      size_t workspace_bytes, void *hip_stream);
+
+/* ---- Double-buffered pass (Sec. 5, "Protocol": quantization and communication are
+ * double buffered so that they overlap with computation).  The vector of p->n values is
+ * cut into chunks of chunk_elems (a multiple of the bucket size).  For every chunk the K
+ * peers' slices g_dev[k] + offset are encoded (peer k with stream_id p->stream_id + k)
+ * on one internal stream, then decoded, summed and applied to x_dev + offset on a second
+ * one, while the next chunk is already being encoded; msg_dev holds 2*K device buffers
+ * of msg_capacity bytes each (two sets used alternately; size them with
+ * qsgd_max_encoded_bytes for n = chunk_elems), and the two workspaces (distinct, each
+ * workspace_bytes >= qsgd_workspace_bytes for n = chunk_elems) serve the encode and the
+ * decode side.  The work starts after what is queued on hip_stream at the time of the
+ * call, and hip_stream continues after the last chunk.  x ends up exactly as after one
+ * qsgd_sgd_step over the K whole-vector messages.  Errors as the calls it is made of;
+ * after an error the internal streams may still hold work: synchronise the device.
+ * qsgd_pipeline_create makes the two streams (default priority) and five events on the
+ * current device; calls on one pipeline object must not overlap. */
+typedef struct qsgd_pipeline qsgd_pipeline;
+int qsgd_pipeline_create(qsgd_pipeline **out);
+void qsgd_pipeline_destroy(qsgd_pipeline *pl);
+int qsgd_pipeline_step(qsgd_pipeline *pl, const qsgd_params *p, uint64_t chunk_elems,
+                       const float *const *g_dev, uint32_t K, float eta, float *x_dev,
+                       void *const *msg_dev, size_t msg_capacity, void *enc_workspace_dev,
+                       void *dec_workspace_dev, size_t workspace_bytes, void *hip_stream);
+
 /* Reads a message header from a HOST copy of (at least) its first 64 bytes.
  * Fills *out (seed is not stored: 0) and *total_bytes (either may be NULL).
  * Returns 0, QSGD_ERR_CORRUPT (not a header), or the status the encoder left

@@ -20,7 +20,8 @@ EXPORTS = [
     "qsgd_timing_reset", "qsgd_timing_get", "qsgd_copy_probe",
     "qsgd_layout_create", "qsgd_layout_destroy", "qsgd_layout_info",
     "qsgd_layout_max_encoded_bytes", "qsgd_layout_workspace_bytes", "qsgd_encode_layout",
-    "qsgd_decode_accumulate_layout", "qsgd_sgd_step_layout",
+    "qsgd_decode_accumulate_layout", "qsgd_sgd_step_layout", "qsgd_encode_slice",
+    "qsgd_pipeline_create", "qsgd_pipeline_destroy", "qsgd_pipeline_step",
 ]
 
 
@@ -115,6 +116,15 @@ def _load():
     L.qsgd_decode_accumulate_layout.restype = C.c_int
     L.qsgd_sgd_step_layout.argtypes = [PP, vp, vp, vp, C.c_uint32, C.c_float, vp, vp, sz, vp]
     L.qsgd_sgd_step_layout.restype = C.c_int
+    L.qsgd_encode_slice.argtypes = [PP, C.c_uint64, vp, vp, sz, vp, sz, vp]
+    L.qsgd_encode_slice.restype = C.c_int
+    L.qsgd_pipeline_create.argtypes = [C.POINTER(vp)]
+    L.qsgd_pipeline_create.restype = C.c_int
+    L.qsgd_pipeline_destroy.argtypes = [vp]
+    L.qsgd_pipeline_destroy.restype = None
+    L.qsgd_pipeline_step.argtypes = [vp, PP, C.c_uint64, vp, C.c_uint32, C.c_float, vp, vp, sz,
+                                     vp, vp, sz, vp]
+    L.qsgd_pipeline_step.restype = C.c_int
     _lib = L
     return L
 
@@ -349,3 +359,65 @@ def qsgd_sgd_step_layout(p: Params, layout: Layout, msgs, eta: float, x, workspa
                                       xp, wp, wbytes, _stream(stream))
     if rc:
         raise QsgdError(rc, "qsgd_sgd_step_layout")
+
+
+def qsgd_encode_slice(p: Params, index_base: int, g, msg, workspace, stream=None) -> None:
+    """Encode of the p.n values in g with the draws of positions index_base.. of a longer vector."""
+    if g.dtype.itemsize != 4 or not g.dtype.is_floating_point or g.numel() != p.n:
+        raise ValueError("g must hold n float32")
+    gp, _ = _dev(g, "g")
+    mp, mbytes = _dev(msg, "msg")
+    wp, wbytes = _dev(workspace, "workspace")
+    cp = p.c()
+    rc = _load().qsgd_encode_slice(C.byref(cp), index_base, gp, mp, mbytes, wp, wbytes,
+                                   _stream(stream))
+    if rc:
+        raise QsgdError(rc, "qsgd_encode_slice")
+
+
+class Pipeline:
+    """Handle of a qsgd_pipeline (two internal streams and their events)."""
+
+    def __init__(self):
+        h = C.c_void_p(0)
+        rc = _load().qsgd_pipeline_create(C.byref(h))
+        if rc:
+            raise QsgdError(rc, "qsgd_pipeline_create")
+        self.handle = h
+
+    def close(self) -> None:
+        if self.handle:
+            _load().qsgd_pipeline_destroy(self.handle)
+            self.handle = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def qsgd_pipeline_step(pipe: Pipeline, p: Params, chunk_elems: int, grads, eta: float, x, msgs,
+                       enc_workspace, dec_workspace, stream=None) -> None:
+    """Queues the double-buffered pass: grads = K device gradients of n values, msgs = 2*K
+    message buffers of equal size (two sets used alternately)."""
+    K = len(grads)
+    if len(msgs) != 2 * K:
+        raise ValueError("msgs must hold 2*K buffers")
+    if x.numel() != p.n or any(g.numel() != p.n for g in grads):
+        raise ValueError("x and the gradients must hold n float32")
+    gptr = (C.c_void_p * K)(*[_dev(g, "g")[0].value for g in grads])
+    mptr = (C.c_void_p * (2 * K))()
+    cap = None
+    for i, m in enumerate(msgs):
+        mp, nbytes = _dev(m, "message")
+        mptr[i] = mp.value
+        cap = nbytes if cap is None else min(cap, nbytes)
+    xp, _ = _dev(x, "x")
+    ep, ebytes = _dev(enc_workspace, "enc_workspace")
+    dp, dbytes = _dev(dec_workspace, "dec_workspace")
+    cp = p.c()
+    rc = _load().qsgd_pipeline_step(pipe.handle, C.byref(cp), chunk_elems, gptr, K, C.c_float(eta),
+                                    xp, mptr, cap, ep, dp, min(ebytes, dbytes), _stream(stream))
+    if rc:
+        raise QsgdError(rc, "qsgd_pipeline_step")

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqsgd.so")
 SOURCES = ["qsgd_capi.hip", "qsgd_encode.hip", "qsgd_decode.hip", "qsgd_general.hip",
-           "qsgd_tensors.hip"]
+           "qsgd_tensors.hip", "qsgd_pipeline.hip"]
 HEADERS = ["qsgd_device.hpp", "qsgd_kernels.hpp", "qsgd_encode_wave.hpp"]
 
 FLAGS = [

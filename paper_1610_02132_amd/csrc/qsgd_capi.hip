@@ -353,13 +353,15 @@ size_t qsgd_workspace_bytes(const qsgd_params* p, uint32_t K) {
   return (size_t)((bytes + 255) & ~(uint64_t)255);
 }
 
-static int encode_impl(const qsgd_params* p, const qsgd_layout* L, const float* g_dev,
-                       void* msg_dev, size_t msg_capacity, void* workspace_dev,
-                       size_t workspace_bytes, void* hip_stream) {
+static int encode_impl(const qsgd_params* p, const qsgd_layout* L, uint64_t index_base,
+                       const float* g_dev, void* msg_dev, size_t msg_capacity,
+                       void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
   Geometry g;
   int rc = layout_geometry(p, L, g);
   if (rc) return rc;
   if (L && !g.bucket_path()) return QSGD_ERR_UNSUPPORTED;
+  if (index_base % 4) return QSGD_ERR_INVALID_ARG;
+  if (index_base && g.n > 0 && !g.bucket_path()) return QSGD_ERR_UNSUPPORTED;
   const uint64_t raw_words = L ? L->raw : 0;
   if (!msg_dev || !aligned16(msg_dev) || !workspace_dev || !aligned16(workspace_dev))
     return QSGD_ERR_INVALID_ARG;
@@ -451,6 +453,7 @@ static int encode_impl(const qsgd_params* p, const qsgd_layout* L, const float* 
   a.norm_mode = g.norm;
   a.btab = L ? L->btab : nullptr;
   a.version = L ? 2 : 1;
+  a.index_base = index_base;
   a.key0 = (uint32_t)p->seed; a.key1 = (uint32_t)(p->seed >> 32);
   a.stream_id = p->stream_id; a.iteration = p->iteration;
   a.bper = pl.bper; a.dst_words = pl.dst_words; a.sub_words = pl.sub_words;
@@ -511,16 +514,23 @@ static int encode_impl(const qsgd_params* p, const qsgd_layout* L, const float* 
 
 int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t msg_capacity,
                 void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
-  return encode_impl(p, nullptr, g_dev, msg_dev, msg_capacity, workspace_dev, workspace_bytes,
-                     hip_stream);
+  return encode_impl(p, nullptr, 0, g_dev, msg_dev, msg_capacity, workspace_dev,
+                     workspace_bytes, hip_stream);
+}
+
+int qsgd_encode_slice(const qsgd_params* p, uint64_t index_base, const float* g_dev,
+                      void* msg_dev, size_t msg_capacity, void* workspace_dev,
+                      size_t workspace_bytes, void* hip_stream) {
+  return encode_impl(p, nullptr, index_base, g_dev, msg_dev, msg_capacity, workspace_dev,
+                     workspace_bytes, hip_stream);
 }
 
 int qsgd_encode_layout(const qsgd_params* p, const qsgd_layout* layout, const float* g_dev,
                        void* msg_dev, size_t msg_capacity, void* workspace_dev,
                        size_t workspace_bytes, void* hip_stream) {
   if (!layout) return QSGD_ERR_INVALID_ARG;
-  return encode_impl(p, layout, g_dev, msg_dev, msg_capacity, workspace_dev, workspace_bytes,
-                     hip_stream);
+  return encode_impl(p, layout, 0, g_dev, msg_dev, msg_capacity, workspace_dev,
+                     workspace_bytes, hip_stream);
 }
 
 

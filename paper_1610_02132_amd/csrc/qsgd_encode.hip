@@ -98,7 +98,7 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
     qc.inv = 0.f; qc.s_f = s_f; qc.s = s; qc.key0 = a.key0; qc.key1 = a.key1;
     qc.stream_id = a.stream_id; qc.iteration = a.iteration;
     uint32_t rall[CPW][4];
-    draw_all<CPW, true>(base + wstart, lane, qc, rall);
+    draw_all<CPW, true>(a.index_base + base + wstart, lane, qc, rall);
     // squares are exact in fp64, so the fused multiply-add rounds like multiply, add
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
 #pragma unroll
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(64) void k_encode_fixed_small(EncodeArgs a) {
     }
 #pragma unroll
     for (int c = 0; c < CP; ++c)
-      draw4<true>(base + (uint64_t)c * kStep + l * 4, qc, r[c]);
+      draw4<true>(a.index_base + base + (uint64_t)c * kStep + l * 4, qc, r[c]);
 
     // ---- scale of each bucket: reduction over its LPB lanes -------------------------
     float scale;

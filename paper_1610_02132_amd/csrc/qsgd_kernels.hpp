@@ -61,6 +61,7 @@ struct EncodeArgs {
   const float* g;
   const uint2* btab;    // per-bucket (start / 4, length) or null
   uint32_t version;     // header version: 1 flat, 2 tensor-aware
+  uint64_t index_base;  // draw index of g[0] (a slice of a longer vector), multiple of 4
   uint64_t n;
   uint32_t d;           // bucket size (<= kMaxBucketFast on this path)
   uint32_t nb;          // number of buckets

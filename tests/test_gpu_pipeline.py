@@ -1,0 +1,78 @@
+"""GPU parity of slice encodes and of the double-buffered pass against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_1610_02132_amd as q  # noqa: E402
+from oracle import qsgd_oracle as qo  # noqa: E402
+
+
+def gradient(n, seed, scale=1e-2):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    return torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, scale, generator=g)
+
+
+@pytest.mark.parametrize("code,s,d", [(q.CODE_SPARSE, 4, 512), (q.CODE_DENSE, 7, 256),
+                                      (q.CODE_FIXED, 256, 512), (q.CODE_SPARSE, 4, 8192)])
+def test_slice_encode_matches_oracle_slice(code, s, d):
+    n, off = 5 * d + 40, 12 * d
+    P = q.Params(n=n, s=s, d=d, code=code, seed=9, stream_id=2, iteration=1)
+    g = gradient(n, 3)
+    cap = q.qsgd_max_encoded_bytes(P)
+    ws = torch.zeros(q.qsgd_workspace_bytes(P, 1) // 4, dtype=torch.int32, device="cuda")
+    msg = torch.zeros(cap // 4, dtype=torch.int32, device="cuda")
+    q.qsgd_encode_slice(P, off, g, msg, ws)
+    status, total = q.qsgd_message_status(msg)
+    assert status == 0
+    got = msg.cpu().numpy().view(np.uint32)[: total // 4]
+    Po = qo.Params(n=n, s=s, d=d, code=code, seed=9, stream_id=2, iteration=1)
+    want = qo.encode_slice(Po, g.cpu().numpy(), off)
+    assert np.array_equal(got, want)
+    # and the draws really moved: the same data at offset 0 gives another message
+    q.qsgd_encode_slice(P, 0, g, msg, ws)
+    status, total0 = q.qsgd_message_status(msg)
+    other = msg.cpu().numpy().view(np.uint32)[: total0 // 4]
+    assert other.size != got.size or not np.array_equal(other, got)
+    with pytest.raises(q.QsgdError):
+        q.qsgd_encode_slice(P, 2, g, msg, ws)
+
+
+@pytest.mark.parametrize("code,s,d,chunk_buckets", [(q.CODE_SPARSE, 4, 512, 64),
+                                                    (q.CODE_FIXED, 256, 512, 100),
+                                                    (q.CODE_SPARSE, 4, 8192, 3),
+                                                    (q.CODE_DENSE, 15, 1024, 7)])
+def test_pipeline_equals_the_flat_step(code, s, d, chunk_buckets):
+    K, eta = 4, 0.1
+    n = 37 * chunk_buckets * d // 10 + 123      # several chunks, a short last one, a short last bucket
+    chunk = chunk_buckets * d
+    P = q.Params(n=n, s=s, d=d, code=code, seed=5, stream_id=0, iteration=3)
+    grads = [gradient(n, 50 + k) for k in range(K)]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    x0 = torch.empty(n, dtype=torch.float32, device="cuda").uniform_(-1, 1, generator=gen)
+    # the oracle: K flat messages, one flat step
+    msgs_o = [qo.encode(qo.Params(n=n, s=s, d=d, code=code, seed=5, stream_id=k, iteration=3),
+                        grads[k].cpu().numpy()) for k in range(K)]
+    want = qo.sgd_step(msgs_o, eta, x0.cpu().numpy())
+    # the pipeline
+    Pc = q.Params(n=min(chunk, n), s=s, d=d, code=code)
+    cap = q.qsgd_max_encoded_bytes(Pc)
+    wsb = q.qsgd_workspace_bytes(Pc, K)
+    msgs = [torch.zeros(cap // 4, dtype=torch.int32, device="cuda") for _ in range(2 * K)]
+    ws_e = torch.zeros(wsb // 4, dtype=torch.int32, device="cuda")
+    ws_d = torch.zeros(wsb // 4, dtype=torch.int32, device="cuda")
+    pipe = q.Pipeline()
+    for rep in range(2):   # the second run reuses buffers and events
+        x = x0.clone()
+        q.qsgd_pipeline_step(pipe, P, chunk, grads, eta, x, msgs, ws_e, ws_d)
+        torch.cuda.synchronize()
+        assert q.qsgd_workspace_status(ws_d) == 0
+        got = x.cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), \
+            f"run {rep}: {np.count_nonzero(got != want)} of {n} values differ"
+    with pytest.raises(q.QsgdError):
+        q.qsgd_pipeline_step(pipe, P, chunk + 4, grads, eta, x, msgs, ws_e, ws_d)
+    pipe.close()
