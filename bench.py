@@ -30,18 +30,19 @@ def hbm_traffic(workload: str, n: int) -> dict:
     """HBM bytes per launch of each kernel, as measured with the hardware counters.
 
     They cannot be collected from inside this process; they come from the committed
-    summary of two `rocprofv3 --pmc` runs of this same command (FETCH_SIZE, then
+    summary of `rocprofv3 --pmc` runs of this same command (FETCH_SIZE, then
     WRITE_SIZE, each scaled by what the counter reads for the copy kernel of known
-    size that this script also launches).  The summary is only used for the
+    size that this script also launches; a third run gives the fraction of time the
+    vector ALU is busy, the roof that binds next to HBM).  The summary is only used for the
     workload and size it was taken on; otherwise traffic is reported as null.
     """
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
-    out = {}
+    out, busy = {}, {}
     try:
         with open(path) as f:
             lines = f.read().splitlines()
     except OSError:
-        return out
+        return out, busy
     size_ok = False
     for line in lines:
         tok = line.split()
@@ -49,7 +50,9 @@ def hbm_traffic(workload: str, n: int) -> dict:
             size_ok = int(tok[1]) == n
         elif len(tok) == 4 and tok[0] == "kernel" and size_ok:
             out[tok[1]] = float(tok[2]) + float(tok[3])   # fetched + written bytes
-    return out
+        elif len(tok) == 3 and tok[0] == "valu_busy" and size_ok:
+            busy[tok[1]] = float(tok[2])                  # vector ALU busy fraction (third run)
+    return out, busy
 
 
 def main() -> int:
@@ -233,10 +236,11 @@ def main() -> int:
     else:
         dom, dom_alg = dec_main, dec_alg
     achieved = dom_alg / (kern[dom]["ms_avg"] * 1e-3) / 1e9
-    traffic = {} if (args.layout or args.pipeline) else hbm_traffic(w.name, n)
+    traffic, valu_busy = ({}, {}) if (args.layout or args.pipeline) else hbm_traffic(w.name, n)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": traffic.get(dom), "bytes_per_launch": dom_alg,
+                "traffic": traffic.get(dom), "valu_busy": valu_busy.get(dom),
+                "bytes_per_launch": dom_alg,
                 "avg_launch_ms": round(kern[dom]["ms_avg"], 4)}
     other, other_alg = (dec_main, dec_alg) if dom == enc_main else (enc_main, enc_alg)
     roofline_other = None
@@ -245,6 +249,7 @@ def main() -> int:
         roofline_other = {"bound": "hbm", "kernel": other, "achieved": round(a2, 1),
                           "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                           "frac": round(a2 / HBM_PEAK_GBPS, 4), "traffic": traffic.get(other),
+                          "valu_busy": valu_busy.get(other),
                           "bytes_per_launch": other_alg,
                           "avg_launch_ms": round(kern[other]["ms_avg"], 4)}
 
