@@ -49,11 +49,13 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 __device__ __forceinline__ uint32_t quantize_one(float v, float inv, float s_f, uint32_t s,
                                                  uint32_t word) {
   const float t = fabsf(v) * inv;
-  const float fl = floorf(t);
-  const float p = t - fl;
+  // t >= 0: the conversion truncates, which is floor(t) (saturating for huge or infinite
+  // t), and the fraction instruction returns t - floor(t), exact and below 1
+  const uint32_t l = (uint32_t)t;
+  const float p = __builtin_amdgcn_fractf(t);
   const float u = (float)(word >> 8) * (1.0f / 16777216.0f);
   // t >= s (a = 1 up to rounding) must give the top level: l + [u < p] >= s then
-  return min((uint32_t)fl + ((u < p) ? 1u : 0u), s);
+  return min(l + ((u < p) ? 1u : 0u), s);
 }
 
 // ---- recursive Elias code (App. A.2): a '0' at the end, binary groups in front ---

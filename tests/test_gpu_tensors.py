@@ -133,3 +133,39 @@ def test_layout_argument_and_capacity_checks():
     with pytest.raises(q.QsgdError):
         q.Layout([(0, 100)], 510, 10)
     L.close()
+
+
+def test_c2_full_tensor_aware():
+    """c2 at its full size as 161 tensors (the bench's --layout mode): two peers' messages
+    byte for byte against the oracle, and the step bit for bit."""
+    w = W.C2
+    tensors, n = arena_of(w.tensors)
+    bypass, K, eta = 10_000, 2, w.eta
+    L = q.Layout(tensors, w.d, bypass)
+    msgs_dev, msgs_host, sizes = [], [], []
+    for k in range(K):
+        flat = W.gradient(w, k, device="cuda")
+        g = torch.zeros(n, dtype=torch.float32, device="cuda")
+        o = 0
+        for off, size in tensors:
+            g[off:off + size] = flat[o:o + size]
+            o += size
+        P = q.Params(n=n, s=w.s, d=w.d, code=w.code, seed=w.seed, stream_id=k)
+        status, total, host, dev = encode_gpu(P, L, g)
+        assert status == 0
+        words = host[: total // 4].copy()
+        check_messages(P, tensors, bypass, g.cpu().numpy(), words)
+        msgs_dev.append(dev)
+        msgs_host.append(words)
+        sizes.append(total)
+    P0 = q.Params(n=n, s=w.s, d=w.d, code=w.code, seed=w.seed)
+    ws = torch.zeros(q.qsgd_layout_workspace_bytes(P0, L, K) // 4, dtype=torch.int32, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3)
+    x0 = torch.empty(n, dtype=torch.float32, device="cuda").uniform_(-1, 1, generator=gen)
+    x = x0.clone()
+    q.qsgd_sgd_step_layout(P0, L, msgs_dev, eta, x, ws, msg_bytes=sizes)
+    assert q.qsgd_workspace_status(ws) == 0
+    want = qo.sgd_step_layout(tensors, bypass, msgs_host, eta, x0.cpu().numpy())
+    assert np.array_equal(x.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    L.close()
