@@ -25,10 +25,10 @@ struct qsgd_layout {
   uint64_t short_buckets = 0; // buckets with fewer than d values ...
   uint64_t short_values = 0;  // ... and the values in them
   uint64_t raw = 0;           // raw fp32 values
-  uint32_t R = 0;             // raw tensors
+  uint32_t R = 0;             // pieces of raw tensors
   int device = 0;
   uint2* btab = nullptr;      // per bucket: (start / 4, length)
-  uint4* rtab = nullptr;      // per raw tensor: (start / 4, length, offset in the raw section, 0)
+  uint4* rtab = nullptr;      // per piece of a raw tensor: (start / 4, length, offset in the raw section, 0)
   std::vector<uint32_t> short_len;  // lengths of the short buckets (size accounting)
 };
 
@@ -584,7 +584,11 @@ int qsgd_layout_create(const uint64_t* offsets, const uint64_t* sizes, uint32_t 
     if (off < prev_end || (off % 4) || off + sz > 0xFFFFFFFFull) { delete L; return QSGD_ERR_INVALID_ARG; }
     prev_end = off + sz;
     if (sz < bypass_below) {
-      if (sz) rt.push_back(make_uint4((uint32_t)(off / 4), (uint32_t)sz, (uint32_t)L->raw, 0));
+      // pieces of kRawPiece values, one workgroup each
+      for (uint64_t o = 0; o < sz; o += kRawPiece)
+        rt.push_back(make_uint4((uint32_t)((off + o) / 4),
+                                (uint32_t)std::min<uint64_t>(kRawPiece, sz - o),
+                                (uint32_t)(L->raw + o), 0));
       L->raw += sz;
       continue;
     }

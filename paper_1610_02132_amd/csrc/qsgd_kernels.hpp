@@ -125,9 +125,10 @@ struct DecodeArgs {
   uint32_t fixed_words_full;
 };
 
-// Raw section of tensor-aware messages: tensor r of the small ones.
+// Raw section of tensor-aware messages: the small tensors in pieces of kRawPiece values.
+constexpr uint32_t kRawPiece = 1024;
 struct RawArgs {
-  const uint4* rtab;         // (start / 4, length, offset in the raw section, 0)
+  const uint4* rtab;         // per piece: (start / 4, length, offset in the raw section, 0)
   uint32_t R;
   uint64_t raw_words;        // all raw values of a message
   uint64_t fixed_strings;    // fixed width: words of all bucket strings; else 0 (read the table)

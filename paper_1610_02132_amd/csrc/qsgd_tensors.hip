@@ -1,7 +1,7 @@
 // Raw section of tensor-aware messages (Sec. 5, "Protocol": matrices with fewer
 // than 10K elements are not quantized).  The small tensors of the arena travel as
-// fp32 words after the bucket strings, in tensor order.  One workgroup per small
-// tensor; they are short by definition, so a simple strided copy is enough.
+// fp32 words after the bucket strings, in tensor order.  One workgroup per piece of
+// kRawPiece values, four values per thread.
 #include "qsgd_device.hpp"
 #include "qsgd_kernels.hpp"
 
@@ -16,7 +16,14 @@ __global__ __launch_bounds__(256) void k_raw_pack(RawArgs a) {
   const uint4 e = a.rtab[blockIdx.x];
   const float* __restrict__ src = a.g + (uint64_t)e.x * 4u;
   uint32_t* __restrict__ dst = a.payload + strings + e.z;
-  for (uint32_t i = threadIdx.x; i < e.y; i += 256) dst[i] = __float_as_uint(src[i]);
+  const uint32_t i = threadIdx.x * 4u;
+  if (i + 3 < e.y) {
+    const float4 v = *reinterpret_cast<const float4*>(src + i);   // tensors start at 16-byte multiples
+    dst[i] = __float_as_uint(v.x); dst[i + 1] = __float_as_uint(v.y);
+    dst[i + 2] = __float_as_uint(v.z); dst[i + 3] = __float_as_uint(v.w);
+  } else {
+    for (uint32_t j = i; j < e.y; ++j) dst[j] = __float_as_uint(src[j]);
+  }
 }
 
 // Decode side: x_i <- x_i + sum_l raw_l[i]  or  x_i <- fma(-c, sum_l raw_l[i], x_i),
@@ -43,11 +50,29 @@ __global__ __launch_bounds__(256) void k_raw_apply(DecodeArgs a, RawArgs r) {
   }
   const uint4 e = r.rtab[blockIdx.x];
   float* __restrict__ x = a.x + (uint64_t)e.x * 4u;
-  for (uint32_t i = threadIdx.x; i < e.y; i += 256) {
-    float sum = 0.f;
-    for (uint32_t k = 0; k < a.K; ++k) sum += __uint_as_float(a.msgs[k][base[k] + e.z + i]);
-    x[i] = a.step ? fmaf(-a.c, sum, x[i]) : x[i] + sum;
+  const uint32_t i0 = threadIdx.x * 4u;
+  if (i0 >= e.y) return;
+  const uint32_t cnt = min(4u, e.y - i0);
+  float sum[4] = {0.f, 0.f, 0.f, 0.f};
+  for (uint32_t k0 = 0; k0 < a.K; k0 += 4) {   // four messages' words in flight, summed in order
+    float w[4][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const uint32_t k = min(k0 + (uint32_t)t, a.K - 1u);
+      const uint32_t* __restrict__ src = a.msgs[k] + base[k] + e.z + i0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[t][j] = (uint32_t)j < cnt ? __uint_as_float(src[j]) : 0.f;
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (k0 + (uint32_t)t < a.K) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sum[j] += w[t][j];
+      }
+    }
   }
+  for (uint32_t j = 0; j < cnt; ++j)
+    x[i0 + j] = a.step ? fmaf(-a.c, sum[j], x[i0 + j]) : x[i0 + j] + sum[j];
 }
 
 // Header (and empty offset table) of a message whose tensors all travel raw.
