@@ -305,6 +305,38 @@ static uint64_t bucket_max_bits(const qo_params *p, uint64_t m) {
   return 64 + 32 * ((m * B + 31) / 32) + 32 * ((m + 31) / 32);
 }
 
+/* Entry points of long strings.  A prefix code can only be read from its start, so
+ * a bucket of millions of values (the sparse regime of Sec. 3.1 uses one bucket
+ * of n) would have to be decoded by a single sequential reader.  When the
+ * bucket size exceeds 8192, a string of an Elias code is therefore followed by
+ * a list of places where a reader may start: positions are cut into segments
+ * of 2048; for segment j >= 1, start_j is the bit offset (in the string, scale
+ * included) of the first record that belongs to a segment >= j and prev_j the
+ * position (1-based, 0 = none) of the last coded coordinate before segment j;
+ * segment j is listed iff floor(start_j / 1024) > floor(start_(j-1) / 1024)
+ * (start_0 = 32) and start_j < 2^32.  After the string's last word come the
+ * listed (start_j, prev_j) pairs as 32-bit words in ascending j and one word
+ * with their count.  This is container metadata of the builder (about 3% of
+ * the string), not part of the paper's code: CONTAINER LAYOUT, PARITY UNPINNED. */
+#define QO_ENTRY_MIN_D 8192u
+#define QO_ENTRY_SEG 2048u
+#define QO_ENTRY_BITS 1024u
+static int has_entries(const qo_params *p) {
+  return p->code != QO_CODE_FIXED && qo_bucket_size(p) > QO_ENTRY_MIN_D;
+}
+
+/* Worst-case words of one bucket string of m elements, entry list included. */
+static uint64_t bucket_max_words(const qo_params *p, uint64_t m) {
+  uint64_t bits = bucket_max_bits(p, m), words = (bits + 31) / 32;
+  if (has_entries(p)) {
+    uint64_t segs = (m + QO_ENTRY_SEG - 1) / QO_ENTRY_SEG;
+    uint64_t e = segs ? segs - 1 : 0;
+    if (bits / QO_ENTRY_BITS < e) e = bits / QO_ENTRY_BITS;
+    words += 2 * e + 1;
+  }
+  return words;
+}
+
 /* Code_s (Sec. 3.1; App. A.2): 32 bits of scale, then for every nonzero level in
  * order: Elias(distance from the previous nonzero; the first distance is the
  * 1-based position), one sign bit (1 = negative), Elias(level).
@@ -316,21 +348,44 @@ static uint64_t code_bucket(const qo_params *p, uint64_t m, float norm,
                             const uint32_t *levels, const uint8_t *neg, bitw *b) {
   uint64_t start_bit = b->pos;
   put_bits(b, float_bits(norm), 32);
-  if (p->code == QO_CODE_SPARSE) {
-    uint64_t prev = 0; /* 1-based position of the previous nonzero */
+  const int entries = has_entries(p);
+  uint32_t *elist = NULL; /* (start, prev) pairs of the listed segments */
+  uint64_t ecount = 0, ecap = 0, start_before = 32;
+  if (p->code == QO_CODE_SPARSE || p->code == QO_CODE_DENSE) {
+    uint64_t prev = 0; /* 1-based position of the previous coded coordinate */
     for (uint64_t i = 1; i <= m; ++i) {
-      if (levels[i - 1] == 0) continue;
-      put_omega(b, i - prev);
-      put_bit(b, neg[i - 1]);
-      put_omega(b, levels[i - 1]);
+      if (entries && i > 1 && (i - 1) % QO_ENTRY_SEG == 0) { /* a segment starts at i */
+        uint64_t start = b->pos - start_bit;
+        if (start / QO_ENTRY_BITS > start_before / QO_ENTRY_BITS && start < (1ull << 32)) {
+          if (ecount == ecap) {
+            ecap = ecap ? 2 * ecap : 64;
+            elist = (uint32_t *)realloc(elist, ecap * 2 * sizeof(uint32_t));
+          }
+          elist[2 * ecount] = (uint32_t)start;
+          elist[2 * ecount + 1] = (uint32_t)prev;
+          ++ecount;
+        }
+        start_before = start;
+      }
+      if (p->code == QO_CODE_SPARSE) {
+        if (levels[i - 1] == 0) continue;
+        put_omega(b, i - prev);
+        put_bit(b, neg[i - 1]);
+        put_omega(b, levels[i - 1]);
+      } else {
+        put_bit(b, neg[i - 1]);
+        put_omega(b, (uint64_t)levels[i - 1] + 1);
+      }
       prev = i;
     }
-    put_bit(b, 1); /* stop marker: records end here (zeros pad the word) */
-  } else if (p->code == QO_CODE_DENSE) {
-    for (uint64_t i = 0; i < m; ++i) {
-      put_bit(b, neg[i]);
-      put_omega(b, (uint64_t)levels[i] + 1);
+    if (p->code == QO_CODE_SPARSE)
+      put_bit(b, 1); /* stop marker: records end here (zeros pad the word) */
+    if (entries) { /* the list follows the string's last word */
+      b->pos = (b->pos + 31) & ~(uint64_t)31;
+      for (uint64_t e = 0; e < 2 * ecount; ++e) put_bits(b, elist[e], 32);
+      put_bits(b, ecount, 32);
     }
+    free(elist);
   } else {
     /* Fixed width.  Word 1 is the escape: index of the one element whose level
      * does not fit the field (it can only be level s), else all ones.  Then
@@ -387,11 +442,11 @@ size_t qo_max_encoded_bytes(const qo_params *p) {
   for (uint64_t b = 0; b < nb; ++b) {
     /* all buckets but the last have the same length: avoid a long loop */
     if (b + 1 < nb) {
-      words += (nb - 1) * ((bucket_max_bits(p, qo_bucket_size(p)) + 31) / 32);
+      words += (nb - 1) * bucket_max_words(p, qo_bucket_size(p));
       b = nb - 2;
       continue;
     }
-    words += (bucket_max_bits(p, bucket_len(p, b)) + 31) / 32;
+    words += bucket_max_words(p, bucket_len(p, b));
   }
   return (size_t)(4 * (H_WORDS + table_words(p) + words));
 }
@@ -571,6 +626,15 @@ static int decode_bucket_m(const view *v, uint64_t b, uint64_t m, float *norm,
   if (rc) return rc;
   if (cnt < 1) return QO_ERR_CORRUPT;
   const uint32_t *w = v->payload + off;
+  /* long buckets: the entry list sits behind the string (see has_entries) */
+  const uint32_t *elist = NULL;
+  uint64_t ecount = 0, enext = 0;
+  if (has_entries(&v->p)) {
+    ecount = w[cnt - 1];
+    if (2 * ecount + 1 >= cnt) return QO_ERR_CORRUPT;
+    cnt -= 2 * ecount + 1;
+    elist = w + cnt;
+  }
   bitr r = {w, cnt * 32, 0, 0};
   uint32_t nbits = 0;
   for (int i = 0; i < 32; ++i) nbits = (nbits << 1) | get_bit(&r); /* the scale */
@@ -591,6 +655,10 @@ static int decode_bucket_m(const view *v, uint64_t b, uint64_t m, float *norm,
     /* positions and values of the nonzeros, until the records are used up */
     uint64_t pos = 0;
     while (r.pos < r.end) {
+      if (enext < ecount && r.pos == elist[2 * enext]) { /* a listed place: it must agree */
+        if (pos != elist[2 * enext + 1]) return QO_ERR_CORRUPT;
+        ++enext;
+      }
       uint64_t gap = get_omega(&r);
       if (r.overrun || gap == 0) return QO_ERR_CORRUPT;
       unsigned sign = get_bit(&r);
@@ -601,14 +669,20 @@ static int decode_bucket_m(const view *v, uint64_t b, uint64_t m, float *norm,
       levels[pos - 1] = (uint32_t)lev;
       neg[pos - 1] = (uint8_t)sign;
     }
+    if (enext != ecount) return QO_ERR_CORRUPT;
   } else if (v->p.code == QO_CODE_DENSE) {
     for (uint64_t i = 0; i < m; ++i) {
+      if (enext < ecount && r.pos == elist[2 * enext]) {
+        if (i != elist[2 * enext + 1]) return QO_ERR_CORRUPT;
+        ++enext;
+      }
       unsigned sign = get_bit(&r);
       uint64_t lev1 = get_omega(&r);
       if (r.overrun || lev1 < 1 || lev1 > (uint64_t)s + 1) return QO_ERR_CORRUPT;
       levels[i] = (uint32_t)(lev1 - 1);
       neg[i] = (uint8_t)sign;
     }
+    if (enext != ecount) return QO_ERR_CORRUPT;
   } else {
     uint32_t B = fixed_bits(s, v->p.norm);
     uint64_t lw = (m * B + 31) / 32, sw = (m + 31) / 32;
@@ -796,12 +870,12 @@ size_t qo_layout_max_encoded_bytes(const qo_params *p, const qo_tensor *t, uint3
                                    uint64_t bypass_below) {
   uint64_t nb, raw;
   if (qo_layout_counts(p, t, T, bypass_below, &nb, &raw)) return 0;
-  uint64_t words = 0, full = (bucket_max_bits(p, p->d) + 31) / 32;
+  uint64_t words = 0, full = bucket_max_words(p, p->d);
   for (uint32_t j = 0; j < T; ++j) {
     if (t[j].size < bypass_below) continue;
     uint64_t q = t[j].size / p->d, r = t[j].size % p->d;
     words += q * full;
-    if (r) words += p->code == QO_CODE_FIXED ? full : (bucket_max_bits(p, r) + 31) / 32;
+    if (r) words += p->code == QO_CODE_FIXED ? full : bucket_max_words(p, r);
   }
   return (size_t)(4 * (H_WORDS + layout_table_words(p, nb) + words + raw));
 }

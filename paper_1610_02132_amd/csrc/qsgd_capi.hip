@@ -61,9 +61,14 @@ struct Geometry {
   uint64_t bucket_len(uint64_t b) const { return std::min(d, n - b * d); }
   // Worst-case words of a bucket string of m elements.
   uint64_t max_words(uint64_t m) const {
-    if (code == QSGD_CODE_SPARSE) return (32 + m * per_elem + 1 + 31) / 32;
-    if (code == QSGD_CODE_DENSE) return (32 + m * per_elem + 31) / 32;
-    return 2 + (m * fixed_bits + 31) / 32 + (m + 31) / 32;
+    if (code == QSGD_CODE_FIXED) return 2 + (m * fixed_bits + 31) / 32 + (m + 31) / 32;
+    const uint64_t bits = 32 + m * per_elem + (code == QSGD_CODE_SPARSE ? 1 : 0);
+    uint64_t words = (bits + 31) / 32;
+    if (d > kEntryMinD) {   // long buckets carry a list of entry points behind the string
+      const uint64_t segs = (m + kSeg - 1) / kSeg;
+      words += 2 * std::min<uint64_t>(segs ? segs - 1 : 0, bits / kEntryBits) + 1;
+    }
+    return words;
   }
   uint64_t max_payload_words() const {
     if (nb == 0) return 0;

@@ -142,6 +142,10 @@ struct RawArgs {
 };
 
 constexpr uint32_t kSeg = 2048;  // values per segment on the general path
+// Elias-coded buckets above kEntryMinD values: the string is followed by a list of places
+// where a reader may start (at most one per kEntryBits bits, on segment boundaries).
+constexpr uint32_t kEntryMinD = 8192;
+constexpr uint32_t kEntryBits = 1024;
 
 struct GenArgs {
   const float* g;

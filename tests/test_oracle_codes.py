@@ -308,3 +308,52 @@ def test_step_rejects_mismatched_messages(qo):
     b = qo.encode(qo.Params(n=101, s=4, d=50), np.ones(101, dtype=np.float32))
     with pytest.raises(qo.OracleError):
         qo.sgd_step([a, b], 0.1, np.zeros(100, dtype=np.float32))
+
+
+@pytest.mark.parametrize("code,s,density,n", [(0, 1, 0.01, 2_000_000), (0, 3, 0.2, 60_000),
+                                              (1, 2, None, 60_000)])
+def test_long_bucket_entry_list_matches_its_definition(qo, code, s, density, n):
+    """Buckets above 8192 values append a list of places where a reader may start.  The
+    string and the list are rebuilt here from the decoded tuple with the pinned code
+    words (qo.omega_string) and the definition: segment j >= 1 of 2048 positions is
+    listed iff floor(start_j / 1024) > floor(start_(j-1) / 1024), with start_j the bit
+    offset of the first record of a segment >= j and prev_j the last coded position
+    before it."""
+    rng = np.random.default_rng(5)
+    g = rng.standard_normal(n).astype(np.float32)
+    if density is not None:   # a few large values: long gaps, few records
+        g *= (rng.random(n) < density) * 50.0 + 0.01
+    p = qo.Params(n=n, s=s, d=n, code=code, seed=3)
+    msg = qo.encode(p, g)
+    tup = qo.decode_tuple(msg)
+    lev, neg = tup["levels"], tup["neg"]
+    bits = format(int(np.float32(tup["norms"][0]).view(np.uint32)), "032b")
+    starts, prevs, prev = {0: 32}, {0: 0}, 0
+    for i in range(1, n + 1):
+        if i > 1 and (i - 1) % 2048 == 0:
+            starts[(i - 1) // 2048] = len(bits)
+            prevs[(i - 1) // 2048] = prev
+        if code == 0:
+            if lev[i - 1] == 0:
+                continue
+            bits += qo.omega_string(i - prev) + ("1" if neg[i - 1] else "0") + qo.omega_string(int(lev[i - 1]))
+        else:
+            bits += ("1" if neg[i - 1] else "0") + qo.omega_string(int(lev[i - 1]) + 1)
+        prev = i
+    if code == 0:
+        bits += "1"
+    bits += "0" * (-len(bits) % 32)
+    want = [int(bits[k:k + 32], 2) for k in range(0, len(bits), 32)]
+    listed = [j for j in range(1, len(starts)) if starts[j] // 1024 > starts[j - 1] // 1024]
+    for j in listed:
+        want += [starts[j], prevs[j]]
+    want.append(len(listed))
+    got = qo.bucket_words(msg, 0)
+    assert len(listed) >= 2                      # the case really has entries
+    assert np.array_equal(got, np.array(want, dtype=np.uint32))
+    # a damaged entry is noticed by the sequential reader
+    bad = msg.copy()
+    off = qo.payload_offset_words(msg) + len(want) - 2     # prev of the last entry
+    bad[off] += 1
+    with pytest.raises(qo.OracleError):
+        qo.decode(bad)
