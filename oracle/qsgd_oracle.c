@@ -669,6 +669,8 @@ static int decode_bucket_m(const view *v, uint64_t b, uint64_t m, float *norm,
       levels[pos - 1] = (uint32_t)lev;
       neg[pos - 1] = (uint8_t)sign;
     }
+    /* segments after the last record are listed at the end of the records */
+    while (enext < ecount && elist[2 * enext] == r.pos && elist[2 * enext + 1] == pos) ++enext;
     if (enext != ecount) return QO_ERR_CORRUPT;
   } else if (v->p.code == QO_CODE_DENSE) {
     for (uint64_t i = 0; i < m; ++i) {

@@ -81,7 +81,8 @@ struct Geometry {
 struct GenPlan {
   uint64_t spb, nseg;
   uint32_t sub_words;
-  uint64_t off_partial, off_scale, off_seginfo, off_segstart, off_seggap, off_slots;
+  uint64_t off_partial, off_scale, off_seginfo, off_segstart, off_seggap, off_segrank,
+      off_segprev, off_bents, off_slots;
   uint64_t enc_bytes;   // encode scratch (after the status block)
   uint64_t dec_bytes;   // decode scratch: dense accumulator
 };
@@ -99,6 +100,9 @@ void plan_general(const Geometry& g, GenPlan& pl) {
   pl.off_seginfo = o; o = align_up(o + 12 * pl.nseg, 256);
   pl.off_segstart = o; o = align_up(o + 8 * pl.nseg, 256);
   pl.off_seggap = o; o = align_up(o + 4 * pl.nseg, 256);
+  pl.off_segrank = o; o = align_up(o + 4 * pl.nseg, 256);
+  pl.off_segprev = o; o = align_up(o + 4 * pl.nseg, 256);
+  pl.off_bents = o; o = align_up(o + 4 * g.nb, 256);
   pl.off_slots = o;
   if (g.code != QSGD_CODE_FIXED) o = align_up(o + 4 * pl.nseg * pl.sub_words, 256);
   pl.enc_bytes = o;
@@ -284,7 +288,7 @@ int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* ms
     }
     float* acc = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + kStatusBytes + kTotalsBytes);
     if (launch_gen_zero(acc, g.n, blocks, st) != hipSuccess) return QSGD_ERR_HIP;
-    if (launch_gen_parse(a, acc, st) != hipSuccess) return QSGD_ERR_HIP;
+    if (launch_gen_parse(a, acc, g.d > kEntryMinD, st) != hipSuccess) return QSGD_ERR_HIP;
     if (launch_gen_apply(a, acc, blocks, st) != hipSuccess) return QSGD_ERR_HIP;
     return QSGD_OK;
   }
@@ -407,6 +411,10 @@ static int encode_impl(const qsgd_params* p, const qsgd_layout* L, uint64_t inde
     a.seginfo = reinterpret_cast<uint32_t*>(wsb + gp.off_seginfo);
     a.segstart = reinterpret_cast<uint64_t*>(wsb + gp.off_segstart);
     a.seggap = reinterpret_cast<uint32_t*>(wsb + gp.off_seggap);
+    a.segrank = reinterpret_cast<uint32_t*>(wsb + gp.off_segrank);
+    a.segprev = reinterpret_cast<uint32_t*>(wsb + gp.off_segprev);
+    a.bents = reinterpret_cast<uint32_t*>(wsb + gp.off_bents);
+    a.entries = (g.code != QSGD_CODE_FIXED && g.d > kEntryMinD) ? 1u : 0u;
     a.slots = reinterpret_cast<uint32_t*>(wsb + gp.off_slots);
     a.fixed_bits = g.fixed_bits;
     a.fixed_words_full = g.max_words(g.d);

@@ -12,10 +12,11 @@
 //            its bucket string (sum-scan), the word offset of every bucket
 //   fill     zeroes the payload
 //   place    per segment: ORs gap code, sub-stream and stop bit into the payload
-// Decode.  One thread per string parses records and adds them to a dense fp32
-// accumulator in the workspace with atomics (with three or more peers hitting the
-// same coordinate the order of the fp32 additions is not fixed); a last kernel
-// applies the accumulator to x.
+// Decode.  Records are added to a dense fp32 accumulator in the workspace, bucket by
+// bucket and inside a bucket message after message (so every coordinate's sum has
+// the order k = 0, 1, ...); a last kernel applies the accumulator to x.  Buckets
+// above 8192 values carry a list of entry points behind their string and are read
+// by a workgroup, a thread per stretch; shorter ones by a thread per bucket.
 #include "qsgd_device.hpp"
 #include "qsgd_encode_wave.hpp"
 #include "qsgd_kernels.hpp"
@@ -242,9 +243,13 @@ __global__ __launch_bounds__(64) void k_gen_encode(GenArgs a) {
 __global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
   __shared__ unsigned long long wave_tot[16];
   __shared__ unsigned long long tmp[1024];
-  __shared__ unsigned long long carry[3];  // max global position, bits in open bucket, words
+  __shared__ unsigned long long carry[5];  // max global position, bits in open bucket, words,
+                                           // bits of the last segment, entries in open bucket
   const int i = threadIdx.x;
-  if (i == 0) { carry[0] = 0; carry[1] = 0; carry[2] = 0; a.table[0] = 0; }
+  if (i == 0) {
+    carry[0] = 0; carry[1] = 0; carry[2] = 0; carry[3] = 0; carry[4] = 0;
+    a.table[0] = 0;
+  }
   __syncthreads();
   const bool sparse = a.code == QSGD_CODE_SPARSE;
   for (uint64_t c0 = 0; c0 < a.nseg; c0 += 1024) {
@@ -257,6 +262,7 @@ __global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
     }
     const unsigned long long base = b * a.d;
     const unsigned long long c_max = carry[0], c_bits = carry[1], c_words = carry[2];
+    const unsigned long long c_tb = carry[3], c_ents = carry[4];
     // which nonzero precedes this segment's first one
     const unsigned long long lastg = (live && first) ? base + last : 0ull;
     const unsigned long long m_incl = block_incl_scan<unsigned long long>(lastg, 0ull, wave_tot, OpMax());
@@ -279,13 +285,42 @@ __global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
     if ((unsigned long long)j <= (unsigned long long)i) before = s_excl - tmp[i - j];
     else before = c_bits + s_excl;
     __syncthreads();
+    // entry list of long buckets: segment j >= 1 is listed iff its bit offset lies in a
+    // later block of kEntryBits bits than the offset of segment j - 1
+    tmp[i] = tb;
+    __syncthreads();
+    const unsigned long long tb_prev = i ? tmp[i - 1] : c_tb;
+    __syncthreads();
+    const unsigned long long start = 32ull + before;
+    const unsigned long long m_b = live ? min((unsigned long long)a.d, a.n - base) : 0ull;
+    const bool listed = a.entries && live && j >= 1 && (unsigned long long)j * kSeg < m_b &&
+                        (start / kEntryBits) > ((start - tb_prev) / kEntryBits) &&
+                        start < (1ull << 32);
+    const unsigned long long e_incl =
+        block_incl_scan<unsigned long long>(listed ? 1ull : 0ull, 0ull, wave_tot, OpSum());
+    const unsigned long long e_excl = e_incl - (listed ? 1ull : 0ull);
+    tmp[i] = e_excl;
+    __syncthreads();
+    unsigned long long rank;  // listed segments of this bucket before this one
+    if ((unsigned long long)j <= (unsigned long long)i) rank = e_excl - tmp[i - j];
+    else rank = c_ents + e_excl;
+    __syncthreads();
     const bool is_end = live && j == a.spb - 1;
+    const unsigned long long ents = rank + (listed ? 1ull : 0ull);  // at the end: of the bucket
     unsigned long long words = 0;
-    if (is_end) words = (32ull + before + tb + (sparse ? 1ull : 0ull) + 31ull) >> 5;
+    if (is_end) {
+      words = (32ull + before + tb + (sparse ? 1ull : 0ull) + 31ull) >> 5;
+      if (a.entries) words += 2ull * ents + 1ull;
+    }
     const unsigned long long w_incl = block_incl_scan<unsigned long long>(words, 0ull, wave_tot, OpSum());
     if (live) {
       a.segstart[seg] = 32ull + before;
       a.seggap[seg] = gap;
+      if (a.entries) {
+        a.segrank[seg] = listed ? (uint32_t)rank : 0xFFFFFFFFu;
+        a.segprev[seg] = sparse ? prev_in_bucket : j * kSeg;
+        if (is_end) a.bents[b] = (uint32_t)ents;
+      }
       if (is_end) {
         const unsigned long long off = c_words + w_incl;
         a.table[b + 1] = off > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)off;
@@ -296,6 +331,8 @@ __global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
       carry[0] = chunk_max > c_max ? chunk_max : c_max;
       carry[1] = is_end ? 0ull : before + tb;
       carry[2] = c_words + w_incl;
+      carry[3] = tb;
+      carry[4] = is_end ? 0ull : ents;
     }
     __syncthreads();
   }
@@ -335,6 +372,17 @@ __global__ __launch_bounds__(64) void k_gen_place(GenArgs a) {
       global_emit(str, start, gc, glen);
     }
     if (j == a.spb - 1 && a.code == QSGD_CODE_SPARSE) global_emit(str, start + glen + bits, 1ull, 1u);
+  }
+  if (a.entries && lane == 0) {
+    // the entry list sits behind the string's last word: pairs, then their count
+    const uint32_t ents = a.bents[b];
+    uint32_t* const list = a.payload + a.table[b + 1] - (2u * ents + 1u);
+    const uint32_t r = a.segrank[seg];
+    if (r != 0xFFFFFFFFu) {
+      list[2u * r] = (uint32_t)start;
+      list[2u * r + 1u] = a.segprev[seg];
+    }
+    if (j == a.spb - 1) list[2u * ents] = ents;
   }
   glen = lane_bcast(glen, 0);
   const uint64_t o = start + glen;
@@ -387,49 +435,134 @@ __global__ __launch_bounds__(256) void k_gen_zero(float* p, uint64_t n) {
     p[i] = 0.f;
 }
 
-__global__ __launch_bounds__(256) void k_gen_parse(DecodeArgs a, float* acc) {
-  if (*a.status != 0) return;
-  const uint64_t idx = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (uint64_t)a.nb * a.K) return;
-  const uint64_t b = idx / a.K;
-  const uint32_t k = (uint32_t)(idx - b * a.K);
-  const uint64_t base = b * (uint64_t)a.d;
-  const uint64_t m = min((uint64_t)a.d, a.n - base);
-  const uint32_t* msg = a.msgs[k];
-  const uint64_t pay = (uint64_t)H_WORDS + a.table_words;
-  const uint32_t o0 = msg[H_WORDS + b], o1 = msg[H_WORDS + b + 1];
-  if (!(o0 < o1 && pay + o1 <= a.msg_words[k])) { flag_corrupt(a.status); return; }
-  const uint32_t* str = msg + pay + o0;
-  const uint64_t nwords = o1 - o0;
-  const float scale = __uint_as_float(str[0]) / (float)a.s;
-  uint64_t endbit = nwords * 32;
-  const bool sparse = a.code == QSGD_CODE_SPARSE;
-  if (sparse) {
-    const uint32_t last = str[nwords - 1];
-    if (last == 0) { flag_corrupt(a.status); return; }
-    endbit = nwords * 32 - 1 - (uint32_t)(__ffs((int)last) - 1);
-    if (endbit < 32) { flag_corrupt(a.status); return; }
-  }
-  uint64_t bitpos = 32, pos = 0;
-  float* out = acc + base;
+// One string, read front to back from (bitpos, pos) until `stop` (or, for the last
+// stretch of a Code'_s string, until position m); values are ADDED to out[] with plain
+// read-modify-writes: the caller guarantees that nobody else touches this bucket's
+// part of out[] at the same time.  Returns false on malformed input.
+__device__ __forceinline__ bool parse_stretch(const uint32_t* str, uint64_t nwords, bool sparse,
+                                              bool to_end_of_bucket, uint64_t stop, uint64_t m,
+                                              uint32_t s, float scale, uint64_t& bitpos,
+                                              uint64_t& pos, float* out) {
   for (;;) {
-    if (sparse ? bitpos >= endbit : pos >= m) break;
+    if (to_end_of_bucket ? pos >= m : bitpos >= stop) return true;
     uint32_t gl = 0, gap = 1;
     if (sparse) {
       gap = omega_loop(peek64(str, nwords, bitpos), gl);
-      if (gap == 0) { flag_corrupt(a.status); return; }
+      if (gap == 0) return false;
     }
     const uint64_t w = peek64(str, nwords, bitpos + gl);
     uint32_t ll;
     uint32_t lev = omega_loop(w << 1, ll);
     bitpos += gl + 1u + ll;
     pos += gap;
-    if (lev == 0 || pos > m || bitpos > endbit) { flag_corrupt(a.status); return; }
+    if (lev == 0 || pos > m || bitpos > stop) return false;
     if (!sparse) lev -= 1u;
-    if (lev > a.s) { flag_corrupt(a.status); return; }
+    if (lev > s) return false;
     if (lev) {
       const float mag = scale * (float)lev;
-      atomicAdd(&out[pos - 1], (w >> 63) ? -mag : mag);
+      out[pos - 1] += (w >> 63) ? -mag : mag;
+    }
+  }
+}
+
+// Where a bucket string of message k lies and where its records end.
+struct StringRef {
+  const uint32_t* str;
+  uint64_t nwords;   // words of the string proper
+  uint64_t endbit;   // records end here
+  const uint32_t* list;
+  uint64_t ents;     // entry points behind the string
+  float scale;
+};
+
+__device__ __forceinline__ bool open_string(const DecodeArgs& a, uint32_t k, uint64_t b,
+                                            bool entries, StringRef& r) {
+  const uint32_t* msg = a.msgs[k];
+  const uint64_t pay = (uint64_t)H_WORDS + a.table_words;
+  const uint32_t o0 = msg[H_WORDS + b], o1 = msg[H_WORDS + b + 1];
+  if (!(o0 < o1 && pay + o1 <= a.msg_words[k])) return false;
+  r.str = msg + pay + o0;
+  uint64_t words = o1 - o0;
+  r.ents = 0;
+  r.list = nullptr;
+  if (entries) {
+    r.ents = r.str[words - 1];
+    if (2 * r.ents + 1 >= words) return false;
+    words -= 2 * r.ents + 1;
+    r.list = r.str + words;
+  }
+  r.nwords = words;
+  r.scale = __uint_as_float(r.str[0]) / (float)a.s;
+  r.endbit = words * 32;
+  if (a.code == QSGD_CODE_SPARSE) {
+    const uint32_t last = r.str[words - 1];
+    if (last == 0) return false;
+    r.endbit = words * 32 - 1 - (uint32_t)(__ffs((int)last) - 1);
+    if (r.endbit < 32) return false;
+  }
+  return true;
+}
+
+// Short buckets of the general path (d <= kEntryMinD, d not a multiple of 4): one thread
+// per bucket reads the K strings one after the other, so every coordinate receives its
+// terms in message order.
+__global__ __launch_bounds__(256) void k_gen_parse(DecodeArgs a, float* acc) {
+  if (*a.status != 0) return;
+  const uint64_t b = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (b >= a.nb) return;
+  const uint64_t base = b * (uint64_t)a.d;
+  const uint64_t m = min((uint64_t)a.d, a.n - base);
+  const bool sparse = a.code == QSGD_CODE_SPARSE;
+  for (uint32_t k = 0; k < a.K; ++k) {
+    StringRef r;
+    if (!open_string(a, k, b, false, r)) { flag_corrupt(a.status); return; }
+    uint64_t bitpos = 32, pos = 0;
+    if (!parse_stretch(r.str, r.nwords, sparse, !sparse, r.endbit, m, a.s, r.scale, bitpos, pos,
+                       acc + base) ||
+        (!sparse && bitpos > r.endbit)) {
+      flag_corrupt(a.status);
+      return;
+    }
+  }
+}
+
+// Long buckets (d > kEntryMinD): the string is followed by a list of entry points, so a
+// workgroup reads one bucket with a thread per stretch between two entries, message
+// after message (a barrier in between): every coordinate receives its terms in message
+// order.  Every stretch must end exactly where the next one starts, at the position
+// the list names.
+__global__ __launch_bounds__(256) void k_gen_parse_entries(DecodeArgs a, float* acc) {
+  if (*a.status != 0) return;
+  __shared__ uint32_t bad;
+  if (threadIdx.x == 0) bad = 0;
+  const uint64_t b = blockIdx.x;
+  const uint64_t base = b * (uint64_t)a.d;
+  const uint64_t m = min((uint64_t)a.d, a.n - base);
+  const bool sparse = a.code == QSGD_CODE_SPARSE;
+  __syncthreads();
+  for (uint32_t k = 0; k < a.K; ++k) {
+    StringRef sr;   // (every thread takes the same decisions here: uniform data)
+    if (!open_string(a, k, b, true, sr)) {
+      if (threadIdx.x == 0) flag_corrupt(a.status);
+      return;
+    }
+    for (uint64_t r = threadIdx.x; r <= sr.ents; r += 256) {
+      uint64_t bitpos = r ? sr.list[2 * (r - 1)] : 32;
+      uint64_t pos = r ? sr.list[2 * (r - 1) + 1] : 0;
+      const bool last_stretch = r == sr.ents;
+      const uint64_t stop = last_stretch ? sr.endbit : sr.list[2 * r];
+      bool ok = bitpos >= 32 && bitpos <= stop && stop <= sr.endbit && pos <= m;
+      ok = ok && parse_stretch(sr.str, sr.nwords, sparse, last_stretch && !sparse, stop, m, a.s,
+                               sr.scale, bitpos, pos, acc + base);
+      // the stretch ends where the next one starts, at the position the list names
+      if (ok && !last_stretch) ok = bitpos == stop && pos == sr.list[2 * r + 1];
+      if (ok && last_stretch && !sparse) ok = pos == m && bitpos <= sr.endbit;
+      if (!ok) bad = 1;
+    }
+    __syncthreads();   // message k is in before message k + 1 adds to the same coordinates
+    if (bad) {
+      if (threadIdx.x == 0) flag_corrupt(a.status);
+      return;
     }
   }
 }
@@ -504,9 +637,12 @@ hipError_t launch_gen_zero(float* p, uint64_t n, uint32_t blocks, hipStream_t st
   hipLaunchKernelGGL(k_gen_zero, dim3(blocks), dim3(256), 0, st, p, n);
   return hipGetLastError();
 }
-hipError_t launch_gen_parse(const DecodeArgs& a, float* acc, hipStream_t st) {
-  const uint64_t strings = (uint64_t)a.nb * a.K;
-  hipLaunchKernelGGL(k_gen_parse, dim3((uint32_t)((strings + 255) / 256)), dim3(256), 0, st, a, acc);
+hipError_t launch_gen_parse(const DecodeArgs& a, float* acc, bool entries, hipStream_t st) {
+  if (entries) {
+    hipLaunchKernelGGL(k_gen_parse_entries, dim3(a.nb), dim3(256), 0, st, a, acc);
+  } else {
+    hipLaunchKernelGGL(k_gen_parse, dim3((a.nb + 255) / 256), dim3(256), 0, st, a, acc);
+  }
   return hipGetLastError();
 }
 hipError_t launch_gen_apply(const DecodeArgs& a, const float* acc, uint32_t blocks, hipStream_t st) {

@@ -166,6 +166,10 @@ struct GenArgs {
   uint32_t* seginfo;   // 3 * nseg: first position, last position, bits
   uint64_t* segstart;  // nseg: bit offset of the segment's gap code in its bucket string
   uint32_t* seggap;    // nseg: gap in front of the segment's first record (0: none)
+  uint32_t* segrank;   // nseg: index of the segment in its bucket's entry list, or ~0
+  uint32_t* segprev;   // nseg: position of the last coded coordinate before the segment
+  uint32_t* bents;     // nb: entries listed by the bucket
+  uint32_t entries;    // 1: strings are followed by an entry list (d > kEntryMinD)
   uint32_t* slots;     // nseg * sub_words
   // fixed width
   uint32_t fixed_bits;
@@ -199,7 +203,7 @@ hipError_t launch_gen_scan(const GenArgs& a, hipStream_t st);
 hipError_t launch_gen_fill(const GenArgs& a, uint32_t blocks, hipStream_t st);
 hipError_t launch_gen_place(const GenArgs& a, hipStream_t st);
 hipError_t launch_gen_zero(float* p, uint64_t n, uint32_t blocks, hipStream_t st);
-hipError_t launch_gen_parse(const DecodeArgs& a, float* acc, hipStream_t st);
+hipError_t launch_gen_parse(const DecodeArgs& a, float* acc, bool entries, hipStream_t st);
 hipError_t launch_gen_apply(const DecodeArgs& a, const float* acc, uint32_t blocks, hipStream_t st);
 hipError_t launch_gen_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t st);
 

@@ -119,7 +119,7 @@ def test_c2_full():
 
 
 def test_c4_full():
-    full_check(W.C4, exact_step=False)  # general path sums with atomics
+    full_check(W.C4)
 
 
 def test_c3_full_sampled():

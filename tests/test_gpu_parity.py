@@ -70,10 +70,10 @@ GENERAL = [  # d > 8192, d not a multiple of 4, d = n: the segmented path
 @pytest.mark.parametrize("w", [g[0] for g in GENERAL], ids=lambda w: w.name)
 @pytest.mark.parametrize("code", [q.CODE_SPARSE, q.CODE_DENSE, q.CODE_FIXED])
 def test_general_path(w, code):
-    # the Elias decode of this path sums with atomics: bit-exactness is not required of it
-    run_case(w, code=code, expect_exact_step=(code == q.CODE_FIXED))
+    # this path too adds every coordinate's terms in message order: x must be bit-identical
+    run_case(w, code=code)
     if code == q.CODE_SPARSE:
-        run_case(w, code=code, norm=q.NORM_MAX, expect_exact_step=False)
+        run_case(w, code=code, norm=q.NORM_MAX)
 
 
 @pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 16, 17, 255, 256, 1000, 65535])
