@@ -435,6 +435,31 @@ __global__ __launch_bounds__(256) void k_gen_zero(float* p, uint64_t n) {
     p[i] = 0.f;
 }
 
+// Four consecutive words of a string in registers (zeros past its end): three serve a
+// 64-bit peek at any bit offset of the first one, the fourth is requested one word
+// ahead of its use so that a reader does not wait for memory at every record.
+struct WordWindow {
+  const uint32_t* str;
+  uint64_t nwords, wi;   // w0..w3 = words wi..wi+3
+  uint32_t w0, w1, w2, w3;
+  __device__ __forceinline__ uint32_t word(uint64_t i) const { return i < nwords ? str[i] : 0u; }
+  __device__ __forceinline__ void open(const uint32_t* s, uint64_t n, uint64_t bitpos) {
+    str = s; nwords = n; wi = bitpos >> 5;
+    w0 = word(wi); w1 = word(wi + 1); w2 = word(wi + 2); w3 = word(wi + 3);
+  }
+  // The 64 stream bits from `bitpos` on; bitpos never moves backwards.
+  __device__ __forceinline__ uint64_t peek(uint64_t bitpos) {
+    while (wi < (bitpos >> 5)) {
+      w0 = w1; w1 = w2; w2 = w3;
+      w3 = word(wi + 4);
+      ++wi;
+    }
+    const uint32_t off = (uint32_t)(bitpos & 31u);
+    const uint64_t hi = ((uint64_t)w0 << 32) | w1;
+    return off ? (hi << off) | (w2 >> (32u - off)) : hi;
+  }
+};
+
 // One string, read front to back from (bitpos, pos) until `stop` (or, for the last
 // stretch of a Code'_s string, until position m); values are ADDED to out[] with plain
 // read-modify-writes: the caller guarantees that nobody else touches this bucket's
@@ -443,25 +468,48 @@ __device__ __forceinline__ bool parse_stretch(const uint32_t* str, uint64_t nwor
                                               bool to_end_of_bucket, uint64_t stop, uint64_t m,
                                               uint32_t s, float scale, uint64_t& bitpos,
                                               uint64_t& pos, float* out) {
+  WordWindow win;
+  win.open(str, nwords, bitpos);
+  // Records are read kBatch at a time and then added together: the additions of one
+  // message hit distinct coordinates, so their loads can all be in flight at once
+  // instead of one memory round trip per record.
+  constexpr int kBatch = 8;
   for (;;) {
-    if (to_end_of_bucket ? pos >= m : bitpos >= stop) return true;
-    uint32_t gl = 0, gap = 1;
-    if (sparse) {
-      gap = omega_loop(peek64(str, nwords, bitpos), gl);
-      if (gap == 0) return false;
+    float* where[kBatch];
+    float what[kBatch];
+    bool done = false;
+#pragma unroll
+    for (int t = 0; t < kBatch; ++t) {
+      where[t] = nullptr;
+      what[t] = 0.f;
+      if (done) continue;
+      if (to_end_of_bucket ? pos >= m : bitpos >= stop) { done = true; continue; }
+      uint32_t gl = 0, gap = 1;
+      if (sparse) {
+        gap = omega_loop(win.peek(bitpos), gl);
+        if (gap == 0) return false;
+      }
+      const uint64_t w = win.peek(bitpos + gl);
+      uint32_t ll;
+      uint32_t lev = omega_loop(w << 1, ll);
+      bitpos += gl + 1u + ll;
+      pos += gap;
+      if (lev == 0 || pos > m || bitpos > stop) return false;
+      if (!sparse) lev -= 1u;
+      if (lev > s) return false;
+      if (lev) {
+        const float mag = scale * (float)lev;
+        where[t] = out + (pos - 1);
+        what[t] = (w >> 63) ? -mag : mag;
+      }
     }
-    const uint64_t w = peek64(str, nwords, bitpos + gl);
-    uint32_t ll;
-    uint32_t lev = omega_loop(w << 1, ll);
-    bitpos += gl + 1u + ll;
-    pos += gap;
-    if (lev == 0 || pos > m || bitpos > stop) return false;
-    if (!sparse) lev -= 1u;
-    if (lev > s) return false;
-    if (lev) {
-      const float mag = scale * (float)lev;
-      out[pos - 1] += (w >> 63) ? -mag : mag;
-    }
+    float old[kBatch];
+#pragma unroll
+    for (int t = 0; t < kBatch; ++t) old[t] = where[t] ? *where[t] : 0.f;
+#pragma unroll
+    for (int t = 0; t < kBatch; ++t)
+      if (where[t]) *where[t] = old[t] + what[t];
+    if (done) return true;
   }
 }
 
