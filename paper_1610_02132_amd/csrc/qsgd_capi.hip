@@ -267,6 +267,11 @@ int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* ms
   a.status = static_cast<uint32_t*>(ws);
   a.fixed_bits = g.fixed_bits;
   a.fixed_words_full = (uint32_t)g.max_words(g.d);
+  // Which apply step the Elias decoder takes.  The share of nonzero levels of Q_s grows
+  // like s / sqrt(d) (Lemma 3.1 (iii)); above 1/8 a string has more records per
+  // 256-position window than the counting apply handles well, and Code'_s has a
+  // record for every coordinate.
+  a.kloop = (g.code == QSGD_CODE_DENSE || 64ull * g.s * g.s > g.d) ? 1u : 0u;
 
   {
     ScopedTiming tm("decode_check", st);
@@ -305,8 +310,8 @@ int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* ms
   uint32_t gw = 1;  // buckets per wavefront: a power of two, gw * K lanes, gw * winp floats
   while (gw * 2 * K <= 64 && gw * 2 <= 16) gw *= 2;
   while (gw > 1 && (g.nb + gw - 1) / gw < (uint64_t)cus * 8) gw /= 2;
-  a.win = win; a.winp = winp; a.gw = gw; a.rec = kRec;
-  const size_t lds = 4 * ((size_t)gw * winp + 64 * a.rec + 64 * (kStrWin + 1) + 64);
+  a.win = win; a.winp = winp; a.gw = gw; a.rec = std::min(16u, 64u / gw);
+  const size_t lds = 4 * ((size_t)gw * winp + 64 * kRec + 64 * (kStrWin + 1) + 64 + 192);
   const uint32_t blocks = (uint32_t)((g.nb + gw - 1) / gw);
   ScopedTiming tm("decode_elias", st);
   if (launch_decode_elias(a, blocks, lds, st) != hipSuccess) return QSGD_ERR_HIP;

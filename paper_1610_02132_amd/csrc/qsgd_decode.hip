@@ -258,14 +258,24 @@ __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
 // measured better than longer rings or windows.
 
 // CODE: sparse or dense Elias code.  LG: groups a level's code word may have.
-template <int CODE, int LG, int NQ>
+// KLOOP: apply the queued records message by message (dense messages) instead of
+// counting the terms of every position first (sparse ones); see the apply step.
+template <int CODE, int LG, int NQ, bool KLOOP>
 __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* acc, uint32_t* queue,
                                                   uint32_t* swin, uint32_t b0, uint32_t gcount) {
   constexpr bool kSparse = CODE == QSGD_CODE_SPARSE;
   // a whole record in one 32-bit peek: gap <= 21 bits, sign, level <= 7 bits
   constexpr bool kNarrow = !kSparse || LG <= 2;
   const uint32_t K = a.K, gw = a.gw, win = a.win, s = a.s;
-  constexpr uint32_t rec = kRec;
+  // ring depth: the message-by-message apply hands ring slot r of string (g, k) to lane
+  // (g, r), so gw * depth <= 64 there
+  constexpr bool kloop = KLOOP;
+  const uint32_t rec = kloop ? a.rec : kRec;
+  // ring slot idx of lane l: lane-major where other lanes read a string's slots side
+  // by side (message loop), slot-major where a lane only reads its own ring
+  auto qidx = [&](uint32_t l, uint32_t idx) -> uint32_t {
+    return kloop ? l * rec + idx : idx * 64u + l;
+  };
   constexpr uint32_t winp = kChunk;  // accumulator stride per bucket
   const int lane = threadIdx.x;
   const uint64_t pay = (uint64_t)H_WORDS + a.table_words;
@@ -401,6 +411,9 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   uint32_t* const accu = reinterpret_cast<uint32_t*>(acc);
   const uint32_t grow = (g < gw ? g : 0u) * winp;   // this lane's accumulator row
   const uint32_t dump = gw * winp + kRec * 64u + 64u * (kStrWin + 1u) + (uint32_t)lane;
+  uint32_t* const counts = accu + gw * winp + kRec * 64u + 64u * (kStrWin + 1u) + 64u;
+  uint32_t* const heads = counts + 64;
+  float* const scales = reinterpret_cast<float*>(counts + 128);
   const uint32_t i = (uint32_t)lane * 4u;
   // x of one window into registers: quad qi is bucket qi of this wavefront.
   auto load_x = [&](float4 (&dst)[NQ], uint32_t ws) {
@@ -464,12 +477,45 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
         const uint32_t trips = __popcll(needy) >= 32 ? rec : kParse;   // dense data: no imbalance
         for (uint32_t np = 0; np < trips && have && qcnt < rec; ++np) {
           if (pend_lev) {
-            queue[((qhead + qcnt) & (rec - 1)) * 64u + lane] =
+            queue[qidx((uint32_t)lane, (qhead + qcnt) & (rec - 1))] =
                 (pend_pos - 1u) | (pend_neg << 13) | (pend_lev << 14);
             ++qcnt;
           }
           advance();
         }
+      }
+      if constexpr (KLOOP) {
+        // Dense data: nearly every ring slot is due in every round, so the records are
+        // applied message by message: in turn kk, lane (g2, r) takes slot r of string
+        // (g2, kk), and all strings of one message run side by side.
+        uint32_t limit = wave_min_u32(have ? pend_pos - 1u : 0xFFFFFFFFu);
+        limit = min(limit, wend);   // 0-based positions below `limit` are due
+        counts[lane] = qcnt;
+        heads[lane] = qhead;
+        scales[lane] = my_scale;
+        __syncthreads();
+        const uint32_t g2 = (uint32_t)lane / rec, r = (uint32_t)lane - g2 * rec;
+        for (uint32_t kk = 0; kk < K; ++kk) {
+          if (g2 < gw) {
+            const uint32_t sl = g2 * K + kk;
+            if (r < counts[sl]) {
+              const uint32_t q = queue[qidx(sl, (heads[sl] + r) & (rec - 1))];
+              const uint32_t p0 = q & 0x1FFFu;
+              if (p0 < limit) {
+                const float mag = scales[sl] * (float)(q >> 14);
+                acc[g2 * winp + ((p0 - ws) & (winp - 1u))] += ((q >> 13) & 1u) ? -mag : mag;
+              }
+            }
+          }
+          __syncthreads();
+        }
+        // drop what was applied from the front of the ring
+        while (qcnt && (queue[qidx((uint32_t)lane, qhead)] & 0x1FFFu) < limit) {
+          qhead = (qhead + 1u) & (rec - 1);
+          --qcnt;
+        }
+        if (limit == wend) break;
+        continue;
       }
       // At most kApply records per lane are applied in a round: a lane that holds
       // more caps the limit at its first record beyond them.
@@ -621,18 +667,19 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   }
 }
 
-template <int CODE, int LG, int NQ>
+template <int CODE, int LG, int NQ, bool KLOOP>
 __global__ __launch_bounds__(64) void k_decode_elias(DecodeArgs a) {
   if (*a.status != 0) return;
   extern __shared__ uint32_t smem[];
-  // LDS: [acc: gw*winp floats][record rings: rec*64][string rings: 64*(kStrWin+1)]
-  const uint32_t gw = a.gw, winp = a.winp, rec = a.rec;
+  // LDS: [acc: gw*winp floats][record rings: kRec*64][string rings: 64*(kStrWin+1)][dump 64]
+  //      [counts 64][heads 64][scales 64]
+  const uint32_t gw = a.gw, winp = a.winp;
   float* const acc = reinterpret_cast<float*>(smem);
   uint32_t* const queue = smem + gw * winp;
-  uint32_t* const swin = queue + 64u * rec;
+  uint32_t* const swin = queue + 64u * kRec;
   const uint32_t b0 = blockIdx.x * gw;
   const uint32_t gcount = min(gw, a.nb - b0);  // buckets this wavefront really has
-  decode_elias_body<CODE, LG, NQ>(a, acc, queue, swin, b0, gcount);
+  decode_elias_body<CODE, LG, NQ, KLOOP>(a, acc, queue, swin, b0, gcount);
 }
 
 hipError_t launch_decode_check(const DecodeArgs& a, hipStream_t st) {
@@ -665,17 +712,24 @@ hipError_t launch_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t
   return hipGetLastError();
 }
 
-template <int CODE, int NQ>
-static hipError_t launch_elias_nq(const DecodeArgs& a, int lg, uint32_t blocks, size_t lds,
+template <int CODE, int NQ, bool KLOOP>
+static hipError_t launch_elias_kl(const DecodeArgs& a, int lg, uint32_t blocks, size_t lds,
                                   hipStream_t st) {
   const dim3 grid(blocks), block(64);
   switch (lg) {
-    case 1: hipLaunchKernelGGL((k_decode_elias<CODE, 1, NQ>), grid, block, lds, st, a); break;
-    case 2: hipLaunchKernelGGL((k_decode_elias<CODE, 2, NQ>), grid, block, lds, st, a); break;
-    case 3: hipLaunchKernelGGL((k_decode_elias<CODE, 3, NQ>), grid, block, lds, st, a); break;
-    default: hipLaunchKernelGGL((k_decode_elias<CODE, 4, NQ>), grid, block, lds, st, a); break;
+    case 1: hipLaunchKernelGGL((k_decode_elias<CODE, 1, NQ, KLOOP>), grid, block, lds, st, a); break;
+    case 2: hipLaunchKernelGGL((k_decode_elias<CODE, 2, NQ, KLOOP>), grid, block, lds, st, a); break;
+    case 3: hipLaunchKernelGGL((k_decode_elias<CODE, 3, NQ, KLOOP>), grid, block, lds, st, a); break;
+    default: hipLaunchKernelGGL((k_decode_elias<CODE, 4, NQ, KLOOP>), grid, block, lds, st, a); break;
   }
   return hipGetLastError();
+}
+
+template <int CODE, int NQ>
+static hipError_t launch_elias_nq(const DecodeArgs& a, int lg, uint32_t blocks, size_t lds,
+                                  hipStream_t st) {
+  return a.kloop ? launch_elias_kl<CODE, NQ, true>(a, lg, blocks, lds, st)
+                 : launch_elias_kl<CODE, NQ, false>(a, lg, blocks, lds, st);
 }
 
 template <int CODE>

@@ -119,7 +119,8 @@ struct DecodeArgs {
   uint32_t gw;           // buckets per wavefront
   uint32_t win;          // window (positions per bucket per pass), multiple of 4
   uint32_t winp;         // accumulator stride per bucket: win rounded up to 256
-  uint32_t rec;          // record slots per string per round
+  uint32_t rec;          // record slots per string (message-by-message apply)
+  uint32_t kloop;        // 1: records are applied message by message (dense messages)
   // fixed width
   uint32_t fixed_bits;
   uint32_t fixed_words_full;

@@ -93,6 +93,18 @@ def test_peer_counts(K):
     run_case(w)
 
 
+@pytest.mark.parametrize("K", [1, 2, 3, 5, 16, 33, 64])
+@pytest.mark.parametrize("d,s", [(2048, 2), (260, 1), (8192, 7), (1024, 3)])
+def test_sparse_messages_counting_apply(K, d, s):
+    """Few records per window (64 s^2 <= d): the Elias decoder counts a position's terms
+    first.  Heavy-tailed data makes positions hit by three and more messages common."""
+    n = d * 9 + d // 3 + 2
+    w = W.Workload(f"cnt{d}_{s}_{K}", n, s, d, q.CODE_SPARSE, K, 0.1, "student_t", (n,))
+    run_case(w)
+    if K == 16:
+        run_case(w, norm=q.NORM_MAX)
+
+
 def test_max_scaling():
     n = 512 * 64 + 12
     for code in (q.CODE_SPARSE, q.CODE_DENSE, q.CODE_FIXED):
