@@ -263,6 +263,7 @@ int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* ms
   a.norm_mode = g.norm; a.table_words = (uint32_t)g.table_words;
   a.btab = L ? L->btab : nullptr;
   a.version = L ? 2 : 1;
+  a.raw_words = L ? L->raw : 0;
   a.x = x_dev; a.c = c; a.step = step;
   a.status = static_cast<uint32_t*>(ws);
   a.fixed_bits = g.fixed_bits;

@@ -76,6 +76,11 @@ __global__ void k_decode_check(DecodeArgs a) {
          h[H_N_LO] == (uint32_t)a.n && h[H_N_HI] == (uint32_t)(a.n >> 32) &&
          h[H_NB_LO] == a.nb && h[H_NB_HI] == 0 && h[H_STATUS] == 0 &&
          (uint64_t)H_WORDS + a.table_words + pw <= a.msg_words[k];
+    if (ok && a.version == 2) {   // tensor-aware: the strings and the raw values fill the payload
+      const uint64_t strings = a.table_words ? (uint64_t)h[H_WORDS + a.nb]
+                                             : (uint64_t)a.nb * a.fixed_words_full;
+      ok = strings + a.raw_words == pw;
+    }
   }
   if (!ok) flag_corrupt(a.status);
 }

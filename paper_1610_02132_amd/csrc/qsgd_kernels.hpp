@@ -104,6 +104,7 @@ struct DecodeArgs {
   uint32_t K;
   const uint2* btab;     // per-bucket (start / 4, length) or null
   uint32_t version;      // header version the messages must carry
+  uint64_t raw_words;    // tensor-aware messages: raw values behind the strings
   uint64_t n;
   uint32_t d;
   uint32_t nb;

@@ -169,3 +169,53 @@ def test_c2_full_tensor_aware():
     want = qo.sgd_step_layout(tensors, bypass, msgs_host, eta, x0.cpu().numpy())
     assert np.array_equal(x.cpu().numpy().view(np.uint32), want.view(np.uint32))
     L.close()
+
+
+def test_corrupt_tensor_aware_messages_are_refused():
+    tensors, n = arena_of([3000, 40, 2500, 7])
+    L = q.Layout(tensors, 512, 100)
+    P = q.Params(n=n, s=4, d=512)
+    g = gradient(n, 9)
+    status, total, host, _ = encode_gpu(P, L, g)
+    assert status == 0
+    ws = torch.zeros(q.qsgd_layout_workspace_bytes(P, L, 1) // 4, dtype=torch.int32, device="cuda")
+    x0 = torch.ones(n, dtype=torch.float32, device="cuda")
+
+    def step(words):
+        msg = torch.from_numpy(words.view(np.int32).copy()).cuda()
+        x = x0.clone()
+        q.qsgd_sgd_step_layout(P, L, [msg], 0.1, x, ws)
+        return q.qsgd_workspace_status(ws), x
+
+    good = host[: total // 4].copy()
+    st, x = step(good)
+    assert st == 0 and not torch.equal(x, x0)
+    for name, edit in [("payload words", lambda w: w.__setitem__(12, w[12] + 1)),
+                       ("bucket count", lambda w: w.__setitem__(10, w[10] + 1)),
+                       ("version", lambda w: w.__setitem__(1, 1)),
+                       ("truncated", None)]:
+        bad = good.copy()
+        if edit is None:
+            bad = bad[:-3].copy()
+        else:
+            edit(bad)
+        st, x = step(bad)
+        assert st != 0, name
+    # a layout with other tensors does not fit the message either
+    L2 = q.Layout([(0, 3000), (3000, 2500)], 512, 100)
+    msg = torch.from_numpy(good.view(np.int32).copy()).cuda()
+    x = x0.clone()
+    ws2 = torch.zeros(q.qsgd_layout_workspace_bytes(P, L2, 1) // 4, dtype=torch.int32, device="cuda")
+    q.qsgd_sgd_step_layout(P, L2, [msg], 0.1, x, ws2)
+    assert q.qsgd_workspace_status(ws2) != 0
+    L.close(); L2.close()
+
+
+def test_copy_probe():
+    src = torch.arange(1 << 20, dtype=torch.float32, device="cuda")
+    dst = torch.zeros_like(src)
+    q.qsgd_copy_probe(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    with pytest.raises(q.QsgdError):
+        q.qsgd_copy_probe(dst[:-1], src[:-1])      # not a multiple of 16 bytes
