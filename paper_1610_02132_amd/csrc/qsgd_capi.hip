@@ -312,7 +312,10 @@ int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* ms
   while (gw * 2 * K <= 64 && gw * 2 <= 16) gw *= 2;
   while (gw > 1 && (g.nb + gw - 1) / gw < (uint64_t)cus * 8) gw /= 2;
   a.win = win; a.winp = winp; a.gw = gw; a.rec = std::min(16u, 64u / gw);
-  const size_t lds = 4 * ((size_t)gw * winp + 64 * kRec + 64 * (kStrWin + 1) + 64 + 192);
+  // LDS: accumulator, record rings, string word rings, dump words; the message-by-message
+  // apply also keeps 3 x 64 words of ring state (the counting apply does not pay for them)
+  const size_t lds = 4 * ((size_t)gw * winp + 64 * kRec + 64 * (kStrWin + 1) + 64 +
+                          (a.kloop ? 192 : 0));
   const uint32_t blocks = (uint32_t)((g.nb + gw - 1) / gw);
   ScopedTiming tm("decode_elias", st);
   if (launch_decode_elias(a, blocks, lds, st) != hipSuccess) return QSGD_ERR_HIP;
