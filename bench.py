@@ -69,6 +69,10 @@ def main() -> int:
     ap.add_argument("--pipeline", type=int, default=0, metavar="CHUNK",
                     help="double-buffered pass: chunks of CHUNK elements (a multiple of d), the "
                          "encodes of one chunk overlapping decode+step of the previous one")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time its replays (for the small, "
+                         "launch-bound workloads); per-kernel times then come from one extra eager "
+                         "step after the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="target CPU time of the oracle baseline sample")
@@ -192,14 +196,35 @@ def main() -> int:
 
     # ---- timed region: exactly --steps steps ---------------------------------------
     q.qsgd_timing_reset()
-    q.qsgd_timing_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
+    if args.graph:
+        if args.pipeline:
+            log("bench.py: --graph and --pipeline do not combine (the pass uses its own streams)")
+            return 2
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            one_step()
+        graph.replay()                      # one untimed replay
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        q.qsgd_timing_enable(True)          # kernel times: one eager step outside the timed region
         one_step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    q.qsgd_timing_enable(False)
+        torch.cuda.synchronize()
+        q.qsgd_timing_enable(False)
+        steps_timed = 1
+    else:
+        q.qsgd_timing_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_step()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        q.qsgd_timing_enable(False)
+        steps_timed = args.steps
     assert q.qsgd_workspace_status(ws2 if args.pipeline else ws) == 0
 
     ms_per_step = 1e3 * elapsed / args.steps
@@ -213,8 +238,8 @@ def main() -> int:
         if cnt:
             kern[name] = {"ms_total": ms, "launches": cnt, "ms_avg": ms / cnt}
     q.qsgd_timing_reset()
-    enc_ms = sum(v["ms_total"] for k_, v in kern.items() if k_.startswith("encode")) / (args.steps * K)
-    dec_ms = sum(v["ms_total"] for k_, v in kern.items() if k_.startswith("decode")) / args.steps
+    enc_ms = sum(v["ms_total"] for k_, v in kern.items() if k_.startswith("encode")) / (steps_timed * K)
+    dec_ms = sum(v["ms_total"] for k_, v in kern.items() if k_.startswith("decode")) / steps_timed
     enc_gbps = 4.0 * n / (enc_ms * 1e-3) / 1e9
     dec_gbps = 4.0 * K * n / (dec_ms * 1e-3) / 1e9
 
@@ -328,7 +353,8 @@ def main() -> int:
                                + (f", tensor-aware ({len(tensors)} tensors, raw below {args.bypass})"
                                   if args.layout else "")
                                + (f", double-buffered in chunks of {args.pipeline}"
-                                  if args.pipeline else ""),
+                                  if args.pipeline else "")
+                               + (", step replayed from a HIP graph" if args.graph else ""),
                    "n": n, "s": w.s, "d": w.d, "K": K, "eta": w.eta,
                    "bits_per_element": round(8 * msg_bytes_avg / n, 4),
                    "message_bytes": int(msg_bytes_avg)},

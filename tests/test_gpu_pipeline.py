@@ -76,3 +76,51 @@ def test_pipeline_equals_the_flat_step(code, s, d, chunk_buckets):
     with pytest.raises(q.QsgdError):
         q.qsgd_pipeline_step(pipe, P, chunk + 4, grads, eta, x, msgs, ws_e, ws_d)
     pipe.close()
+
+
+def test_step_is_graph_capturable_and_replays_identically():
+    """The library only launches kernels on the caller's stream (no allocation, no
+    synchronisation, no memset nodes), so a step can be captured into a HIP graph; every
+    replay must give what the eager calls give."""
+    n, d, s, K, eta = 512 * 300 + 40, 512, 4, 3, 0.1
+    P = [q.Params(n=n, s=s, d=d, seed=2, stream_id=k) for k in range(K)]
+    grads = [gradient(n, 20 + k) for k in range(K)]
+    cap = q.qsgd_max_encoded_bytes(P[0])
+    ws = torch.zeros(q.qsgd_workspace_bytes(P[0], K) // 4, dtype=torch.int32, device="cuda")
+    msgs = [torch.zeros(cap // 4, dtype=torch.int32, device="cuda") for _ in range(K)]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    x0 = torch.empty(n, dtype=torch.float32, device="cuda").uniform_(-1, 1, generator=gen)
+
+    def one_step(x):
+        for k in range(K):
+            q.qsgd_encode(P[k], grads[k], msgs[k], ws)
+        q.qsgd_sgd_step(P[0], msgs, eta, x, ws)
+
+    x_eager = x0.clone()
+    one_step(x_eager)
+    one_step(x_eager)          # two steps: x moves twice
+    torch.cuda.synchronize()
+    x_graph = x0.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        one_step(x_graph.clone())              # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_step(x_graph)
+    for rep in range(2):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert q.qsgd_workspace_status(ws) == 0    # eager work and a sync between replays
+    assert torch.equal(x_graph, x_eager)
+    # a third and fourth replay against two more eager steps
+    one_step(x_eager)
+    one_step(x_eager)
+    graph.replay()
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(x_graph, x_eager)
