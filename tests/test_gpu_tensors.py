@@ -219,3 +219,17 @@ def test_copy_probe():
     assert torch.equal(dst, src)
     with pytest.raises(q.QsgdError):
         q.qsgd_copy_probe(dst[:-1], src[:-1])      # not a multiple of 16 bytes
+
+
+@pytest.mark.parametrize("seed", range(int(__import__("os").environ.get("QSGD_RANDOM_CASES", "24"))))
+def test_random_layouts(seed):
+    rng = np.random.default_rng(500 + seed)
+    T = int(rng.integers(1, 40))
+    sizes = [int(rng.choice([1, 3, 7, 100, 511, 512, 513, 4000, 10_000, 33_333, 70_001])) *
+             int(rng.integers(1, 3)) for _ in range(T)]
+    d = int(rng.choice([4, 64, 256, 512, 1000, 1024, 2048, 4096, 8192]))
+    s = int(rng.choice([1, 2, 4, 15, 16, 256, 1000]))
+    code = int(rng.integers(0, 3))
+    norm = int(rng.integers(0, 2))
+    bypass = int(rng.choice([0, 1, 100, 1000, 10_000, 10**9]))
+    test_layout_encode_and_step_match_oracle((f"rl{seed}", sizes, d, s, code, norm, bypass))
