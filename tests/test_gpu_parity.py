@@ -64,6 +64,10 @@ GENERAL = [  # d > 8192, d not a multiple of 4, d = n: the segmented path
     (W.Workload("g1", 333, 7, 1, q.CODE_SPARSE, 2, 0.1, "normal", (333,)), None),
     (W.Workload("g9999", 9999 * 4 + 5, 3, 9999, q.CODE_SPARSE, 5, 0.1, "student_t", (40001,)), None),
     (W.Workload("g70001", 70001, 256, 70001, q.CODE_SPARSE, 2, 0.1, "normal", (70001,)), None),
+    # more than 1024 segments: the single-workgroup scan takes several passes, and buckets
+    # (5 and 9 segments each, entry lists) straddle its pass boundaries
+    (W.Workload("g10000x300", 10000 * 300 + 77, 4, 10000, q.CODE_SPARSE, 2, 0.1, "student_t", (3000077,)), None),
+    (W.Workload("g17000x150", 17000 * 150 + 5, 16, 17000, q.CODE_SPARSE, 2, 0.1, "normal", (2550005,)), None),
 ]
 
 
