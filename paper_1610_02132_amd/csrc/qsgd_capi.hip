@@ -459,7 +459,7 @@ static int encode_impl(const qsgd_params* p, const qsgd_layout* L, uint64_t inde
   EncodePlan pl;
   int tw, cpw;
   team_shape(g.d, tw, cpw);
-  const uint32_t target = std::min<uint32_t>(kMaxTeams, (uint32_t)device_cus() * (32u / tw));
+  const uint32_t target = std::min<uint32_t>(kMaxTeams, (uint32_t)device_cus() * (QSGD_ENC_TEAMS / tw));
   plan_encode(g, target, pl);
   if (workspace_bytes < kStatusBytes + pl.ws_bytes) return QSGD_ERR_CAPACITY;
   // fixed width: the size of the message does not depend on the data

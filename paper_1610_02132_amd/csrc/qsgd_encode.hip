@@ -39,7 +39,7 @@ __device__ __forceinline__ float4 load_quad(const float* __restrict__ gb, uint32
 
 // TW wavefronts per bucket, each holding up to CPW chunks of 256 elements.
 template <int TW, int CPW, int CODE>
-__global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE == 2 ? 1 : 4))) void k_encode_bucket(EncodeArgs a) {
+__global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE == 2 ? 1 : QSGD_ENC_WAVES))) void k_encode_bucket(EncodeArgs a) {
   extern __shared__ uint32_t smem[];
   // LDS: [dst image of the bucket string][TW sub-streams][TW record rings][scratch]
   constexpr uint32_t kRingW = (CODE == QSGD_CODE_SPARSE) ? kRingWords : 0u;

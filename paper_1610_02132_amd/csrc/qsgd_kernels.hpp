@@ -10,6 +10,16 @@ namespace qsgd {
 
 constexpr uint32_t kMaxBucketFast = 8192;  // largest bucket the register path holds
 constexpr uint32_t kMaxTeams = 8192;       // most teams (regions) one encode uses
+// Team encoder of the Elias codes: waves per SIMD the compiler budgets registers for, and
+// wavefronts of persistent teams per compute unit.  Measured on c5: 4 / 32 -> 0.63 ms per
+// 5e8 values, 4 / 96 -> 0.61, 6 / 96 -> 0.54 (a few spilled registers cost less than the
+// extra wavefronts bring).
+#ifndef QSGD_ENC_WAVES
+#define QSGD_ENC_WAVES 6
+#endif
+#ifndef QSGD_ENC_TEAMS
+#define QSGD_ENC_TEAMS 96u
+#endif
 #ifndef QSGD_FIXED_BPC
 #define QSGD_FIXED_BPC 128  // fixed-width decode: workgroups per compute unit
 #endif
