@@ -499,7 +499,7 @@ static int encode_impl(const qsgd_params* p, const qsgd_layout* L, uint64_t inde
     const int cp = (int)((g.d + lpb * 4 - 1) / (lpb * 4));
     const uint32_t per_pass = 64u / lpb;
     const uint32_t groups = (uint32_t)((g.nb + per_pass - 1) / per_pass);
-    const uint32_t want = std::min<uint32_t>(kMaxTeams, (uint32_t)device_cus() * 32u);
+    const uint32_t want = (uint32_t)device_cus() * QSGD_FS_TEAMS;   // (no per-team state: no cap)
     const uint32_t t = std::max(1u, std::min(groups, want));
     a.bper = (groups + t - 1) / t;
     const uint32_t teams = (groups + a.bper - 1) / a.bper;
