@@ -26,7 +26,7 @@ constexpr uint32_t kMaxTeams = 8192;       // most teams (regions) one encode us
 #define QSGD_FS_TEAMS 1024u
 #endif
 #ifndef QSGD_FIXED_BPC
-#define QSGD_FIXED_BPC 128  // fixed-width decode: workgroups per compute unit
+#define QSGD_FIXED_BPC 512  // fixed-width decode: workgroups per compute unit
 #endif
 #ifndef QSGD_FIXED_KG
 #define QSGD_FIXED_KG 8     // fixed-width decode: messages requested together
