@@ -36,7 +36,8 @@ namespace {
 
 using namespace qsgd;
 
-constexpr uint64_t kTotalsBytes = (uint64_t)kMaxTeams * 4;  // workspace: team totals
+// workspace: words appended by each team (u32) and their exclusive prefix sums (u64)
+constexpr uint64_t kTotalsBytes = (uint64_t)kMaxTeams * 4 + (uint64_t)kMaxTeams * 8;
 constexpr uint64_t kStatusBytes = 256;                      // workspace: decode status word
 
 uint32_t omega_len_host(uint64_t k) {
@@ -521,6 +522,7 @@ static int encode_impl(const qsgd_params* p, const qsgd_layout* L, uint64_t inde
   if (g.code != QSGD_CODE_FIXED) {
     CompactArgs c;
     c.staging = a.staging; c.region_words = pl.region_words; c.totals = a.totals;
+    c.prefix = reinterpret_cast<unsigned long long*>(wsb + (uint64_t)kMaxTeams * 4);
     c.table = table; c.payload = payload; c.header = header; c.cap_words = cap_words;
     c.bper = pl.bper; c.nb = (uint32_t)g.nb; c.table_words = (uint32_t)g.table_words;
     c.raw_words = raw_words;

@@ -453,19 +453,39 @@ __global__ __launch_bounds__(64) void k_encode_fixed_small(EncodeArgs a) {
   }
 }
 
-// Moves each team's region to its place in the message: base_j = sum of the
-// totals of the teams before j.  One workgroup per team.
+// Exclusive prefix sums of the teams' totals: one workgroup, up to kMaxTeams values.
+__global__ __launch_bounds__(1024) void k_encode_prefix(CompactArgs a, uint32_t teams) {
+  __shared__ unsigned long long wave_tot[16];
+  __shared__ unsigned long long carry;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) carry = 0;
+  __syncthreads();
+  for (uint32_t c0 = 0; c0 < teams; c0 += 1024) {
+    const uint32_t i = c0 + tid;
+    const unsigned long long v = i < teams ? a.totals[i] : 0ull;
+    unsigned long long incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const unsigned long long up = __shfl_up(incl, o, kWave);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    unsigned long long before = carry;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    if (i < teams) a.prefix[i] = before + incl - v;
+    __syncthreads();
+    if (tid == 1023) carry = before + incl;
+    __syncthreads();
+  }
+}
+
+// Moves each team's region to its place in the message: base_j = words of the teams
+// before j (k_encode_prefix).  One workgroup per team.
 __global__ __launch_bounds__(256) void k_encode_compact(CompactArgs a) {
-  __shared__ unsigned long long part[4];
   const int tid = threadIdx.x;
   const uint32_t j = blockIdx.x;
-  unsigned long long acc = 0;
-  for (uint32_t i = tid; i < j; i += 256) acc += a.totals[i];
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, kWave);
-  if ((tid & 63) == 0) part[tid >> 6] = acc;
-  __syncthreads();
-  const uint64_t base = part[0] + part[1] + part[2] + part[3];
+  const uint64_t base = a.prefix[j];
   const uint32_t mine = a.totals[j];
   const uint32_t b_begin = j * a.bper;
   const uint32_t b_end = min(b_begin + a.bper, a.nb);
@@ -561,6 +581,7 @@ hipError_t launch_encode_fixed_small(const EncodeArgs& a, int lpb, int cp, uint3
 }
 
 hipError_t launch_encode_compact(const CompactArgs& a, uint32_t teams, hipStream_t st) {
+  hipLaunchKernelGGL(k_encode_prefix, dim3(1), dim3(1024), 0, st, a, teams);
   hipLaunchKernelGGL(k_encode_compact, dim3(teams), dim3(256), 0, st, a);
   return hipGetLastError();
 }

@@ -103,6 +103,7 @@ struct CompactArgs {
   const uint32_t* staging;
   uint64_t region_words;
   const uint32_t* totals;
+  unsigned long long* prefix;  // workspace: words appended by the teams before each team
   uint32_t* table;
   uint32_t* payload;
   uint32_t* header;
