@@ -43,19 +43,54 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+// The same block when c1, c2 and c3 are equal in all lanes (c0 is not).  Then the second
+// product of round one and the first product of round two depend on wave-uniform values
+// alone; stating that (readfirstlane) moves them to the scalar unit, two of the twenty
+// 32 x 32 -> 64 bit multiplies, which are the expensive instructions here.
+__device__ __forceinline__ void philox4x32_10_uniform(uint32_t c0, uint32_t c1, uint32_t c2,
+                                                      uint32_t c3, uint32_t k0, uint32_t k1,
+                                                      uint32_t out[4]) {
+  asm volatile("" : "+s"(k0), "+s"(k1));
+  c1 = __builtin_amdgcn_readfirstlane(c1);
+  c2 = __builtin_amdgcn_readfirstlane(c2);
+  c3 = __builtin_amdgcn_readfirstlane(c3);
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);
+    const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
+    if (r == 0) n0 = __builtin_amdgcn_readfirstlane((uint32_t)(p1 >> 32) ^ c1 ^ k0);
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
 // ---- Q_s on one coordinate (Eq. 2) ---------------------------------------------
 // t = |v| * fl(s/scale) = a*s;  l = floor(t);  p = t - l;  level = l + [u < p],
 // u = (word >> 8) * 2^-24;  t >= s (a = 1 up to rounding) gives the top level.
-__device__ __forceinline__ uint32_t quantize_one(float v, float inv, float s_f, uint32_t s,
-                                                 uint32_t word) {
-  const float t = fabsf(v) * inv;
+// quantize_unclamped leaves out the clamp: its result exceeds s (by one) only for t >= s.
+__device__ __forceinline__ uint32_t quantize_unclamped(float v, float inv, uint32_t word) {
+  // |v| * inv = |v * inv| (inv >= 0); the absolute value then rides on the operands of
+  // the two instructions that read t instead of costing one of its own
+  const float ts = v * inv;
   // t >= 0: the conversion truncates, which is floor(t) (saturating for huge or infinite
   // t), and the fraction instruction returns t - floor(t), exact and below 1
-  const uint32_t l = (uint32_t)t;
-  const float p = __builtin_amdgcn_fractf(t);
+  const uint32_t l = (uint32_t)fabsf(ts);
+  const float p = __builtin_amdgcn_fractf(fabsf(ts));
   const float u = (float)(word >> 8) * (1.0f / 16777216.0f);
+  return l + ((u < p) ? 1u : 0u);
+}
+
+__device__ __forceinline__ uint32_t quantize_one(float v, float inv, float s_f, uint32_t s,
+                                                 uint32_t word) {
   // t >= s (a = 1 up to rounding) must give the top level: l + [u < p] >= s then
-  return min(l + ((u < p) ? 1u : 0u), s);
+  return min(quantize_unclamped(v, inv, word), s);
 }
 
 // ---- recursive Elias code (App. A.2): a '0' at the end, binary groups in front ---
@@ -114,7 +149,9 @@ __device__ __forceinline__ void global_emit(uint32_t* words, uint64_t bitoff, ui
 // is the identity of every combination used here (sums, max of magnitudes).
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ uint32_t dpp_fetch(uint32_t v) {
-  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+  // all rows written: lanes without a source read 0 by themselves (bound_ctrl), so no
+  // register has to be cleared for them first
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, ROW_MASK == 0xf);
 }
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ uint32_t dpp_fetch_or(uint32_t other, uint32_t v) {  // `other` where no source

@@ -16,6 +16,9 @@
 #include "qsgd_encode_wave.hpp"
 #include "qsgd_kernels.hpp"
 
+#ifndef QSGD_UHI
+#define QSGD_UHI 1
+#endif
 namespace qsgd {
 
 namespace {
@@ -291,7 +294,8 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
 // the per-bucket work (scale reduction, square root, divide) is shared by the
 // buckets that ride in one wavefront.
 template <int LPB, int CP, int B>
-__global__ __launch_bounds__(64) void k_encode_fixed_small(EncodeArgs a) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QSGD_FS_WAVES)))
+void k_encode_fixed_small(EncodeArgs a) {
   constexpr int NB = 64 / LPB;             // buckets per wavefront pass
   constexpr uint32_t kStep = LPB * 4;      // values one pass of the bucket's lanes covers
   constexpr uint32_t fmax = (1u << B) - 1u;
@@ -346,9 +350,17 @@ __global__ __launch_bounds__(64) void k_encode_fixed_small(EncodeArgs a) {
         }
       }
     }
+    {
+      const uint64_t g0 = a.index_base + base + l * 4;
+      uint32_t hi;
+      if (QSGD_UHI && uniform_counter_hi(g0, g0 + (uint64_t)(CP - 1) * kStep, hi)) {
 #pragma unroll
-    for (int c = 0; c < CP; ++c)
-      draw4<true>(a.index_base + base + (uint64_t)c * kStep + l * 4, qc, r[c]);
+        for (int c = 0; c < CP; ++c) draw4_uniform_hi(g0 + (uint64_t)c * kStep, hi, qc, r[c]);
+      } else {
+#pragma unroll
+        for (int c = 0; c < CP; ++c) draw4<true>(g0 + (uint64_t)c * kStep, qc, r[c]);
+      }
+    }
 
     // ---- scale of each bucket: reduction over its LPB lanes -------------------------
     float scale;
@@ -392,20 +404,25 @@ __global__ __launch_bounds__(64) void k_encode_fixed_small(EncodeArgs a) {
     uint32_t* const lplane = str + 2;
     uint32_t* const splane = lplane + lw;
     uint32_t esc = 0xFFFFFFFFu;
+    const uint32_t zlim = min(fmax, s);
 #pragma unroll
     for (int c = 0; c < CP; ++c) {
       const uint32_t e0 = (uint32_t)c * kStep + l * 4;
       uint32_t z[4];
-      z[0] = quantize_one(v[c].x, inv, s_f, s, r[c][0]);
-      z[1] = quantize_one(v[c].y, inv, s_f, s, r[c][1]);
-      z[2] = quantize_one(v[c].z, inv, s_f, s, r[c][2]);
-      z[3] = quantize_one(v[c].w, inv, s_f, s, r[c][3]);
+      z[0] = quantize_unclamped(v[c].x, inv, r[c][0]);
+      z[1] = quantize_unclamped(v[c].y, inv, r[c][1]);
+      z[2] = quantize_unclamped(v[c].z, inv, r[c][2]);
+      z[3] = quantize_unclamped(v[c].w, inv, r[c][3]);
       const uint32_t nib = (v[c].x < 0.f ? 1u : 0u) | (v[c].y < 0.f ? 2u : 0u) |
                            (v[c].z < 0.f ? 4u : 0u) | (v[c].w < 0.f ? 8u : 0u);
-      if (max(max(z[0], z[1]), max(z[2], z[3])) > fmax) {  // level s with s = 2^B: rare
+      // rare: a level above s (clamped to s here) or one the field cannot hold (level s
+      // with s = 2^B, which goes to the escape word)
+      if (max(max(z[0], z[1]), max(z[2], z[3])) > zlim) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 4; ++j) {
+          z[j] = min(z[j], s);
           if (z[j] > fmax) { esc = e0 + j; z[j] = fmax; }
+        }
       }
       if (B == 8) {
         const uint32_t wi = e0 >> 2;

@@ -66,6 +66,22 @@ __device__ __forceinline__ void draw4(uint64_t gidx, const QuantCtx& q, uint32_t
   }
 }
 
+// True when every Philox block of the elements gidx_first .. gidx_last (each lane passes
+// its own lowest and highest index) has the same high counter word in all lanes: always,
+// unless the wavefront straddles a multiple of 2^34 elements.  `hi` receives that word.
+__device__ __forceinline__ bool uniform_counter_hi(uint64_t gidx_first, uint64_t gidx_last,
+                                                   uint32_t& hi) {
+  hi = __builtin_amdgcn_readfirstlane((uint32_t)(gidx_first >> 34));
+  return __builtin_amdgcn_ballot_w64((uint32_t)(gidx_first >> 34) != hi ||
+                                     (uint32_t)(gidx_last >> 34) != hi) == 0;
+}
+
+// draw4 of an aligned block whose high counter word `hi` is the same in every lane.
+__device__ __forceinline__ void draw4_uniform_hi(uint64_t gidx, uint32_t hi, const QuantCtx& q,
+                                                 uint32_t r[4]) {
+  philox4x32_10_uniform((uint32_t)(gidx >> 2), hi, q.stream_id, q.iteration, q.key0, q.key1, r);
+}
+
 // Draw words of every chunk a wavefront holds.  They do not depend on the data, so
 // callers compute them while the loads of the values are still in flight.
 template <int CPW, bool ALIGNED>

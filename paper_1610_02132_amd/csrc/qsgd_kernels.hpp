@@ -25,6 +25,10 @@ constexpr uint32_t kMaxTeams = 8192;       // most teams (regions) one encode us
 #ifndef QSGD_FS_TEAMS
 #define QSGD_FS_TEAMS 1024u
 #endif
+// ... and waves per SIMD its registers are budgeted for (c3, in the benchmark: 5 -> 0.168 ms, 6 -> 0.163, 7 -> 0.169 on one box).
+#ifndef QSGD_FS_WAVES
+#define QSGD_FS_WAVES 6
+#endif
 #ifndef QSGD_FIXED_BPC
 #define QSGD_FIXED_BPC 512  // fixed-width decode: workgroups per compute unit
 #endif

@@ -17,8 +17,11 @@ def gradient(n, seed, scale=1e-2):
 
 @pytest.mark.parametrize("code,s,d", [(q.CODE_SPARSE, 4, 512), (q.CODE_DENSE, 7, 256),
                                       (q.CODE_FIXED, 256, 512), (q.CODE_SPARSE, 4, 8192)])
-def test_slice_encode_matches_oracle_slice(code, s, d):
-    n, off = 5 * d + 40, 12 * d
+@pytest.mark.parametrize("high", [False, True])
+def test_slice_encode_matches_oracle_slice(code, s, d, high):
+    # high: the third bucket straddles element 2^34, where the second Philox counter word
+    # changes in the middle of a wavefront
+    n, off = 5 * d + 40, ((1 << 34) - 2 * d - 256 if high else 12 * d)
     P = q.Params(n=n, s=s, d=d, code=code, seed=9, stream_id=2, iteration=1)
     g = gradient(n, 3)
     cap = q.qsgd_max_encoded_bytes(P)
