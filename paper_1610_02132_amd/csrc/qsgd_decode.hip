@@ -443,9 +443,11 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   };
   // Order of the memory operations (the wait counter retires them in order): the
   // x values of window w+1 are requested at the start of window w and used at the
-  // end of window w+1; the strings are topped up at the end of a window, BEFORE
-  // that window's stores, so that waiting for string words never waits for a
-  // store or for the x values requested after them.
+  // end of window w+1; the next piece of a string is requested into registers at the
+  // top of a parse round (sparse messages) and at the end of a window, BEFORE that
+  // window's stores, and moved into the ring at the top of the following round, so
+  // that waiting for string words never waits for a store or for x values requested
+  // after them, and a round's own work hides their latency.
   uint32_t tw[kStrFetch], tw_base = 0;   // string words on their way: [tw_base, tw_base + kStrFetch)
   bool tw_pending = false;
   auto commit_pending = [&]() {
@@ -455,6 +457,17 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       sfill += kStrFetch;
     }
     tw_pending = false;
+  };
+  // Requests the next piece of the string into registers; commit_pending() moves it
+  // into the ring later, so the round in between hides the latency.
+  auto request_next = [&]() {
+    tw_pending = have && sfill < nwords && sfill - nwi <= kStrWin - kStrFetch;
+    tw_base = sfill;
+#pragma unroll
+    for (uint32_t j = 0; j < kStrFetch; ++j) {
+      const uint32_t idx = sfill + j;
+      tw[j] = (tw_pending && idx < nwords) ? str[idx] : 0u;
+    }
   };
   float4 xr[NQ], xn[NQ];
   load_x(xr, 0);
@@ -478,7 +491,12 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       if (needy != 0 || nroom >= kParseLanes) {
         // top up the string rings together, then parse
         commit_pending();
-        if (have && sfill < nwords && sfill - nwi <= kStrWin - kStrFetch) fetch();
+        if constexpr (KLOOP) {
+          // dense strings use up a piece in a round or two: have it now
+          if (have && sfill < nwords && sfill - nwi <= kStrWin - kStrFetch) fetch();
+        } else {
+          request_next();   // arrives while this round parses and applies
+        }
         const uint32_t trips = __popcll(needy) >= 32 ? rec : kParse;   // dense data: no imbalance
         for (uint32_t np = 0; np < trips && have && qcnt < rec; ++np) {
           if (pend_lev) {
@@ -629,13 +647,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     }
     // ---- string words requested a window ago arrive; request the next ones ---------------
     commit_pending();
-    tw_pending = have && sfill < nwords && sfill - nwi <= kStrWin - kStrFetch;
-    tw_base = sfill;
-#pragma unroll
-    for (uint32_t j = 0; j < kStrFetch; ++j) {
-      const uint32_t idx = sfill + j;
-      tw[j] = (tw_pending && idx < nwords) ? str[idx] : 0u;
-    }
+    request_next();
     // ---- combine the accumulator with x and store ------------------------------------
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
