@@ -315,7 +315,8 @@ int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* ms
   a.win = win; a.winp = winp; a.gw = gw; a.rec = std::min(16u, 64u / gw);
   // LDS: accumulator, record rings, string word rings, dump words; the message-by-message
   // apply also keeps 3 x 64 words of ring state (the counting apply does not pay for them)
-  const size_t lds = 4 * ((size_t)gw * winp + 64 * kRec + 64 * (kStrWin + 1) + 64 +
+  a.q16 = (g.code == QSGD_CODE_SPARSE && !a.kloop && g.s <= 4) ? 1u : 0u;
+  const size_t lds = 4 * ((size_t)gw * winp + rec_words(a.q16 != 0) + 64 * (kStrWin + 1) + 64 +
                           (a.kloop ? 192 : 0));
   const uint32_t blocks = (uint32_t)((g.nb + gw - 1) / gw);
   ScopedTiming tm("decode_elias", st);

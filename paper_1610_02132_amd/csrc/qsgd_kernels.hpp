@@ -43,6 +43,9 @@ constexpr uint32_t kStrWin = QSGD_STR_WIN;  // Elias decode: words of a string a
 #define QSGD_REC 16
 #endif
 constexpr uint32_t kRec = QSGD_REC;               // Elias decode: records a lane queues ahead
+// LDS words of a wavefront's record rings: a record is (position, sign, level); with
+// s <= 4 it fits 16 bits (13 + 1 + 2, the level stored minus one), else it takes 32.
+__host__ __device__ constexpr uint32_t rec_words(bool q16) { return q16 ? 32u * kRec : 64u * kRec; }
 #ifndef QSGD_APPLY
 #define QSGD_APPLY 8
 #endif
@@ -142,6 +145,7 @@ struct DecodeArgs {
   uint32_t winp;         // accumulator stride per bucket: win rounded up to 256
   uint32_t rec;          // record slots per string (message-by-message apply)
   uint32_t kloop;        // 1: records are applied message by message (dense messages)
+  uint32_t q16;          // 1: 16-bit records (counting apply, s <= 4)
   // fixed width
   uint32_t fixed_bits;
   uint32_t fixed_words_full;
