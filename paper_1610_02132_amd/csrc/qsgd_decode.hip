@@ -251,8 +251,8 @@ __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
 
 // ---- Elias codes: one lane per string, gw buckets x K messages per wavefront -------
 // The bucket is walked in windows of `win` (<= 256) positions.  Per wavefront:
-//  (1) x of the NEXT window is requested into registers, a whole window ahead of
-//      its use;
+//  (1) x of a window is requested into registers well ahead of its use (at the
+//      start of the window, or a whole window earlier: see kAhead);
 //  (2) every lane parses ahead into its own ring of records.  Its string comes
 //      through a small per-lane ring of words in LDS that is refilled in pieces
 //      (a 128-byte line of a message is then fetched a few times, not once per
@@ -451,13 +451,12 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       }
     }
   };
-  // Order of the memory operations (the wait counter retires them in order): the
-  // x values of window w+1 are requested at the start of window w and used at the
-  // end of window w+1; the next piece of a string is requested into registers at the
-  // top of a parse round (sparse messages) and at the end of a window, BEFORE that
-  // window's stores, and moved into the ring at the top of the following round, so
-  // that waiting for string words never waits for a store or for x values requested
-  // after them, and a round's own work hides their latency.
+  // Order of the memory operations (the wait counter retires them in order): the x
+  // values are requested at the start of a window and used at its end; the next piece
+  // of a string is requested into registers at the top of a parse round (counting apply)
+  // and at the end of a window, BEFORE that window's stores, and moved into the ring at
+  // the top of the following round, so that waiting for string words never waits for a
+  // store, and a round's own work hides their latency and that of the x values.
   uint32_t tw[kStrFetch], tw_base = 0;   // string words on their way: [tw_base, tw_base + kStrFetch)
   bool tw_pending = false;
   auto commit_pending = [&]() {
@@ -479,11 +478,20 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       tw[j] = (tw_pending && idx < nwords) ? str[idx] : 0u;
     }
   };
+  // Message-by-message apply: x is requested a whole window ahead, because its rounds
+  // wait for string words at once and would wait for x with them.  Counting apply: the
+  // string words of a round arrive a round later, so x is requested at the start of its
+  // own window and one register set is enough (one more wavefront per SIMD).
+  constexpr bool kAhead = KLOOP;
   float4 xr[NQ], xn[NQ];
-  load_x(xr, 0);
+  if constexpr (kAhead) load_x(xr, 0);
   for (uint32_t ws = 0; ws < a.d; ws += win) {
     const uint32_t wend = ws + win;  // positions (1-based) up to wend fall in this window
-    if (wend < a.d) load_x(xn, wend);
+    if constexpr (kAhead) {
+      if (wend < a.d) load_x(xn, wend);
+    } else {
+      load_x(xr, ws);
+    }
     // ---- rounds: parse ahead into the rings, apply what is due --------------------------
     // A position may only be applied once EVERY string has been parsed past it,
     // or an element could receive message 5's term before message 2's.  `limit`
@@ -689,7 +697,8 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       }
     }
 #pragma unroll
-    for (int qi = 0; qi < NQ; ++qi) xr[qi] = xn[qi];
+    for (int qi = 0; qi < NQ; ++qi)
+      if constexpr (kAhead) xr[qi] = xn[qi];
     __syncthreads();
   }
 }
