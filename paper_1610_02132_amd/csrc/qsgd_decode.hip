@@ -18,8 +18,6 @@
 
 namespace qsgd {
 
-
-
 namespace {
 
 // Recursive Elias code (App. A.2), decoder rule unrolled: N = 1; a 0 bit outputs N,
@@ -140,7 +138,7 @@ __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
         xv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
         acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
         if (e0 + 3 < m) {
-          xv[c] = *reinterpret_cast<const float4*>(xp);
+          xv[c] = load_stream(xp);
         } else if (e0 < m) {
           xv[c].x = xp[0];
           if (e0 + 1 < m) xv[c].y = xp[1];
@@ -238,7 +236,7 @@ __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
           v.x += acc[c][0]; v.y += acc[c][1]; v.z += acc[c][2]; v.w += acc[c][3];
         }
         if (e0 + 3 < m) {
-          *reinterpret_cast<float4*>(xp) = v;
+          store_stream(xp, v);
         } else if (e0 < m) {
           xp[0] = v.x;
           if (e0 + 1 < m) xp[1] = v.y;
@@ -442,7 +440,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
         const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
         const float* xp = a.x + base + ws + i;
         if (i + 3 < cntw) {
-          dst[qi] = *reinterpret_cast<const float4*>(xp);
+          dst[qi] = load_stream(xp);
         } else {
           if (i + 0 < cntw) dst[qi].x = xp[0];
           if (i + 1 < cntw) dst[qi].y = xp[1];
@@ -687,7 +685,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
             xv.x += av.x; xv.y += av.y; xv.z += av.z; xv.w += av.w;
           }
           if (i + 3 < cntw) {
-            *reinterpret_cast<float4*>(xp) = xv;
+            store_stream(xp, xv);
           } else {
             xp[0] = xv.x;
             if (i + 1 < cntw) xp[1] = xv.y;

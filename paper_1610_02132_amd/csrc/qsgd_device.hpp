@@ -142,6 +142,19 @@ __device__ __forceinline__ void global_emit(uint32_t* words, uint64_t bitoff, ui
   if (sh + len > 64u) atomicOr(&words[w + 2], (uint32_t)top << (32u - sh));
 }
 
+// ---- streaming accesses ----------------------------------------------------------
+// For data that is touched once (the gradient, x): the caches then keep what is
+// touched again, such as message strings read piece by piece.
+typedef float v4f __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream(const float* p) {
+  const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream(float* p, const float4& x) {
+  v4f v; v.x = x.x; v.y = x.y; v.z = x.z; v.w = x.w;
+  __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
+}
+
 // ---- wavefront helpers ----------------------------------------------------------
 // Cross-lane data movement uses DPP modifiers (row shifts inside rows of 16 lanes,
 // then broadcasts of lane 15 / lane 31 into the following rows): one VALU

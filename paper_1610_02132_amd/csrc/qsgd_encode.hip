@@ -29,7 +29,7 @@ __device__ __forceinline__ float4 load_quad(const float* __restrict__ gb, uint32
                                             uint32_t m) {
   float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
   if (eoff + 3 < m) {
-    v = *reinterpret_cast<const float4*>(gb + eoff);
+    v = load_stream(gb + eoff);  // read once: the team's staged strings stay cached
   } else {
     if (eoff + 0 < m) v.x = gb[eoff + 0];
     if (eoff + 1 < m) v.y = gb[eoff + 1];
