@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -156,6 +157,7 @@ struct EncodePlan {
   uint32_t teams, bper;
   uint64_t region_words;
   uint32_t dst_words, sub_words;
+  uint32_t ring;   // records in a wavefront's survivor ring (Code_s)
   size_t lds;
   uint64_t ws_bytes;
 };
@@ -177,7 +179,15 @@ void plan_encode(const Geometry& g, uint32_t teams_target, EncodePlan& pl) {
     pl.sub_words = (uint32_t)(((sub_bits + 31) / 32 + 2 + 1) & ~(uint64_t)1);
     pl.ws_bytes = kTotalsBytes + (uint64_t)pl.teams * pl.region_words * 4;
   }
-  const size_t ring_words = g.code == QSGD_CODE_SPARSE ? kRingWords : 0;
+  // Survivor ring of Code_s: the small one where several wavefronts share a bucket and the
+  // expected share of nonzero levels, at most s (s + sqrt(d)) / d (Lemma 3.1 (iii)), is
+  // below 1/8: a chunk of 256 values then hardly ever brings the 66 survivors that make
+  // a wavefront start over, and a compute unit holds one more team.
+  pl.ring = kRing;
+  if (g.code == QSGD_CODE_SPARSE && pl.tw >= 2 &&
+      8.0 * g.s * (g.s + std::sqrt((double)g.d)) <= (double)g.d)
+    pl.ring = kRingSmall;
+  const size_t ring_words = g.code == QSGD_CODE_SPARSE ? qsgd::ring_words(pl.ring) : 0;
   pl.lds = 4 * ((size_t)pl.dst_words + (size_t)pl.tw * (pl.sub_words + ring_words)) + 8 * pl.tw +
            16 * pl.tw + 16;
 }
@@ -480,7 +490,7 @@ static int encode_impl(const qsgd_params* p, const qsgd_layout* L, uint64_t inde
   a.index_base = index_base;
   a.key0 = (uint32_t)p->seed; a.key1 = (uint32_t)(p->seed >> 32);
   a.stream_id = p->stream_id; a.iteration = p->iteration;
-  a.bper = pl.bper; a.dst_words = pl.dst_words; a.sub_words = pl.sub_words;
+  a.bper = pl.bper; a.dst_words = pl.dst_words; a.sub_words = pl.sub_words; a.ring = pl.ring;
   a.header = header; a.table = table;
   a.totals = reinterpret_cast<uint32_t*>(wsb);
   a.staging = reinterpret_cast<uint32_t*>(wsb + kTotalsBytes);

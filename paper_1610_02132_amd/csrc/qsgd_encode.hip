@@ -41,11 +41,12 @@ __device__ __forceinline__ float4 load_quad(const float* __restrict__ gb, uint32
 }  // namespace
 
 // TW wavefronts per bucket, each holding up to CPW chunks of 256 elements.
-template <int TW, int CPW, int CODE>
+// RING: records in a wavefront's survivor ring (Code_s only; see kRingSmall).
+template <int TW, int CPW, int CODE, uint32_t RING = kRing>
 __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE == 2 ? 1 : QSGD_ENC_WAVES))) void k_encode_bucket(EncodeArgs a) {
   extern __shared__ uint32_t smem[];
   // LDS: [dst image of the bucket string][TW sub-streams][TW record rings][scratch]
-  constexpr uint32_t kRingW = (CODE == QSGD_CODE_SPARSE) ? kRingWords : 0u;
+  constexpr uint32_t kRingW = (CODE == QSGD_CODE_SPARSE) ? ring_words(RING) : 0u;
   uint32_t* const dst = smem;
   uint32_t* const sub_all = smem + a.dst_words;
   uint32_t* const ring_all = sub_all + TW * a.sub_words;
@@ -223,10 +224,28 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
     {
       const uint32_t wlen = wstart < m ? min((uint32_t)CPW * kChunk, m - wstart) : 0u;
       const int nchunks = (int)((wlen + kChunk - 1) / kChunk);
-      if (CODE == QSGD_CODE_SPARSE)
-        encode_sparse_wave<CPW, false>(v, rall, nchunks, wstart, lane, qc, ring, sub, wo);
-      else
+      if (CODE == QSGD_CODE_SPARSE) {
+        const bool gave_up =
+            encode_sparse_wave<CPW, false, RING>(v, rall, nchunks, wstart, lane, qc, ring, sub, wo);
+        if (RING < kRing && gave_up) {
+          // dense data after all: clear what the sub-stream holds and code the wavefront's
+          // values chunk by chunk straight from memory
+          const uint32_t dirty = min(a.sub_words, ((wo.bits + 31u) >> 5) + 2u);
+          for (uint32_t j = lane; j < dirty; j += kWave) sub[j] = 0;
+          wo.first_pos = 0; wo.last_pos = 0; wo.bits = 0;
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll 1
+          for (int c = 0; c < nchunks; ++c) {
+            const uint32_t e0 = wstart + (uint32_t)c * kChunk + (uint32_t)lane * 4u;
+            const float4 vc = load_quad(gb, e0, m);
+            uint32_t rc[4];
+            draw4<true>(a.index_base + base + e0, qc, rc);
+            encode_sparse_direct<false>(vc, rc, e0 + 1u, lane, qc, sub, wo);
+          }
+        }
+      } else {
         encode_dense_wave<CPW>(v, rall, nchunks, wlen, lane, qc, sub, wo);
+      }
     }
     const uint32_t wbits = wo.bits;
 
@@ -548,8 +567,12 @@ static hipError_t launch_tw_cpw(const EncodeArgs& a, uint32_t code, dim3 grid, s
                                 hipStream_t st) {
   switch (code) {
     case QSGD_CODE_SPARSE:
-      hipLaunchKernelGGL((k_encode_bucket<TW, CPW, QSGD_CODE_SPARSE>), grid, dim3(64 * TW), lds,
-                         st, a);
+      if (TW >= 2 && a.ring == kRingSmall)
+        hipLaunchKernelGGL((k_encode_bucket<TW, CPW, QSGD_CODE_SPARSE, TW >= 2 ? kRingSmall : kRing>),
+                           grid, dim3(64 * TW), lds, st, a);
+      else
+        hipLaunchKernelGGL((k_encode_bucket<TW, CPW, QSGD_CODE_SPARSE>), grid, dim3(64 * TW), lds,
+                           st, a);
       break;
     case QSGD_CODE_DENSE:
       hipLaunchKernelGGL((k_encode_bucket<TW, CPW, QSGD_CODE_DENSE>), grid, dim3(64 * TW), lds,

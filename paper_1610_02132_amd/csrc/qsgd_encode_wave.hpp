@@ -18,8 +18,14 @@
 
 namespace qsgd {
 
-constexpr uint32_t kRing = 256;  // records in a wavefront's ring (power of two)
-constexpr uint32_t kRingWords = 3 * kRing;
+// Records in a wavefront's ring (a power of two).  256 holds the survivors of a whole chunk
+// whatever the data.  128 is for teams of several wavefronts on sparse data, where LDS
+// decides how many teams a compute unit holds: a chunk that might not fit (more than
+// 128 - 63 survivors) then makes the wavefront start over with encode_sparse_direct.
+constexpr uint32_t kRing = 256;
+constexpr uint32_t kRingSmall = 128;
+__host__ __device__ constexpr uint32_t ring_words(uint32_t ring) { return 3u * ring; }
+constexpr uint32_t kRingWords = ring_words(kRing);
 
 struct QuantCtx {
   float inv;   // fl(s / scale), 0 for an all-zero bucket
@@ -94,19 +100,19 @@ __device__ __forceinline__ void draw_all(uint64_t gidx0, int lane, const QuantCt
 
 // Stage 2 on `take` (1..64) records starting at ring slot `head`.
 // WIDE: gaps may need more than 21 bits, emit gap and (sign, level) separately.
-template <bool WIDE>
+template <bool WIDE, uint32_t RING = kRing>
 __device__ __forceinline__ void sparse_flush(const uint32_t* ring, uint32_t head, uint32_t take,
                                              int lane, const QuantCtx& q, uint32_t* sub,
                                              WaveOut& out) {
-  const uint32_t idx = (head + (uint32_t)lane) & (kRing - 1);
+  const uint32_t idx = (head + (uint32_t)lane) & (RING - 1);
   const bool live = (uint32_t)lane < take;
   uint32_t pos = 0, len = 0, gl = 0, cl = 0;
   uint64_t gc = 0, cw = 0;
   if (live) {
     pos = ring[idx];
-    const float ts = __uint_as_float(ring[kRing + idx]);
-    const uint32_t word = ring[2 * kRing + idx];
-    const uint32_t prev = lane == 0 ? out.last_pos : ring[(idx - 1u) & (kRing - 1)];
+    const float ts = __uint_as_float(ring[RING + idx]);
+    const uint32_t word = ring[2 * RING + idx];
+    const uint32_t prev = lane == 0 ? out.last_pos : ring[(idx - 1u) & (RING - 1)];
     const float t = fabsf(ts);
     const float fl = floorf(t);
     const float p = t - fl;
@@ -141,8 +147,10 @@ __device__ __forceinline__ void sparse_flush(const uint32_t* ring, uint32_t head
 //   rall      draw words of every chunk (draw_all)
 //   ring      kRingWords words of LDS private to this wavefront
 //   sub       zero-initialised LDS words private to this wavefront
-template <int CPW, bool WIDE>
-__device__ __forceinline__ void encode_sparse_wave(const float4 (&v)[CPW],
+// Returns true when it gave up (RING < 256 only): the sub-stream and `out` then hold
+// leftovers and the caller starts over with encode_sparse_direct.
+template <int CPW, bool WIDE, uint32_t RING = kRing>
+__device__ __forceinline__ bool encode_sparse_wave(const float4 (&v)[CPW],
                                                    const uint32_t (&rall)[CPW][4], int nchunks,
                                                    uint32_t pos0, int lane,
                                                    const QuantCtx& q, uint32_t* ring,
@@ -164,11 +172,16 @@ __device__ __forceinline__ void encode_sparse_wave(const float4 (&v)[CPW],
     const uint32_t cnt = (uint32_t)(__popcll(mk[0]) + __popcll(mk[1]) + __popcll(mk[2]) +
                                     __popcll(mk[3]));
     if (cnt == 0) continue;
-    while (count + cnt > kRing) {  // make room (only in very dense data)
-      const uint32_t take = min(64u, count);
-      sparse_flush<WIDE>(ring, head, take, lane, q, sub, out);
-      head += take;
-      count -= take;
+    if constexpr (RING >= 256) {
+      while (count + cnt > RING) {  // make room (only in very dense data)
+        const uint32_t take = min(64u, count);
+        sparse_flush<WIDE, RING>(ring, head, take, lane, q, sub, out);
+        head += take;
+        count -= take;
+      }
+    } else {
+      // the ring holds at most 63 records here
+      if (cnt > RING - 63u) return true;
     }
     uint32_t slot = head + count + bits_below(mk[0]) + bits_below(mk[1]) + bits_below(mk[2]) +
                     bits_below(mk[3]);
@@ -176,17 +189,17 @@ __device__ __forceinline__ void encode_sparse_wave(const float4 (&v)[CPW],
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if (nz[j]) {
-        const uint32_t i = slot & (kRing - 1);
+        const uint32_t i = slot & (RING - 1);
         ring[i] = p1 + j;
-        ring[kRing + i] = __float_as_uint(ts[j]);
-        ring[2 * kRing + i] = r[j];
+        ring[RING + i] = __float_as_uint(ts[j]);
+        ring[2 * RING + i] = r[j];
         ++slot;
       }
     }
     count += cnt;
     __builtin_amdgcn_wave_barrier();
     while (count >= 64u) {
-      sparse_flush<WIDE>(ring, head, 64u, lane, q, sub, out);
+      sparse_flush<WIDE, RING>(ring, head, 64u, lane, q, sub, out);
       head += 64u;
       count -= 64u;
     }
@@ -194,9 +207,81 @@ __device__ __forceinline__ void encode_sparse_wave(const float4 (&v)[CPW],
   __builtin_amdgcn_wave_barrier();
   while (count > 0) {
     const uint32_t take = min(64u, count);
-    sparse_flush<WIDE>(ring, head, take, lane, q, sub, out);
+    sparse_flush<WIDE, RING>(ring, head, take, lane, q, sub, out);
     head += take;
     count -= take;
+  }
+  return false;
+}
+
+// Inclusive prefix maximum over the 64 lanes.
+__device__ __forceinline__ uint32_t wave_incl_max_u32(uint32_t v) {
+  v = max(v, dpp_fetch<kDppShr1, 0xf>(v));
+  v = max(v, dpp_fetch<kDppShr2, 0xf>(v));
+  v = max(v, dpp_fetch<kDppShr4, 0xf>(v));
+  v = max(v, dpp_fetch<kDppShr8, 0xf>(v));
+  v = max(v, dpp_fetch<kDppBcast15, 0xa>(v));
+  v = max(v, dpp_fetch<kDppBcast31, 0xc>(v));
+  return v;
+}
+
+// Code_s of one chunk without the ring, for dense data: every lane codes its own four
+// values (Eq. 2, then gap, sign, level); the position of the nonzero level before a lane's
+// first one comes from a prefix maximum over the lanes.  Appends to `sub` and `out` like
+// encode_sparse_wave.  p1: 1-based bucket position of the lane's first value.
+template <bool WIDE>
+__device__ __forceinline__ void encode_sparse_direct(const float4& v, const uint32_t (&r)[4],
+                                                     uint32_t p1, int lane, const QuantCtx& q,
+                                                     uint32_t* sub, WaveOut& out) {
+  const float vv[4] = {v.x, v.y, v.z, v.w};
+  uint32_t z[4], lastnz = 0, firstnz = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    z[j] = quantize_one(vv[j], q.inv, q.s_f, q.s, r[j]);
+    if (z[j]) {
+      lastnz = p1 + j;
+      if (!firstnz) firstnz = p1 + j;
+    }
+  }
+  const uint32_t incl_max = wave_incl_max_u32(lastnz);
+  uint32_t prev = (uint32_t)__shfl_up((int)incl_max, 1);
+  if (lane == 0) prev = 0;
+  prev = max(prev, out.last_pos);   // 0: no record in this sub-stream yet
+  uint64_t gc[4], cw[4];
+  uint32_t gl[4], cl[4], tot = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    gc[j] = 0; cw[j] = 0; gl[j] = 0; cl[j] = 0;
+    if (z[j]) {
+      const uint32_t pos = p1 + j;
+      if (prev != 0) omega_encode(pos - prev, gc[j], gl[j]);
+      uint64_t lc; uint32_t ll;
+      omega_encode(z[j], lc, ll);
+      cw[j] = ((uint64_t)(vv[j] < 0.f ? 1u : 0u) << ll) | lc;
+      cl[j] = ll + 1u;
+      prev = pos;
+      tot += gl[j] + cl[j];
+    }
+  }
+  const uint32_t incl = wave_incl_scan_u32(tot, lane);
+  uint32_t off = out.bits + incl - tot;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (cl[j]) {
+      if (WIDE) {
+        if (gl[j]) lds_emit(sub, off, gc[j], gl[j]);
+        lds_emit(sub, off + gl[j], cw[j], cl[j]);
+      } else {
+        lds_emit(sub, off, (gc[j] << cl[j]) | cw[j], gl[j] + cl[j]);
+      }
+      off += gl[j] + cl[j];
+    }
+  }
+  out.bits += lane_bcast(incl, 63);
+  const uint64_t any = __ballot(firstnz != 0);
+  if (any) {
+    if (out.first_pos == 0) out.first_pos = lane_bcast(firstnz, __ffsll((unsigned long long)any) - 1);
+    out.last_pos = lane_bcast(incl_max, 63);
   }
 }
 

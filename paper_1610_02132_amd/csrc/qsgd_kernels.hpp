@@ -13,12 +13,13 @@ constexpr uint32_t kMaxTeams = 8192;       // most teams (regions) one encode us
 // Team encoder of the Elias codes: waves per SIMD the compiler budgets registers for, and
 // wavefronts of persistent teams per compute unit.  Measured on c5: 4 / 32 -> 0.63 ms per
 // 5e8 values, 4 / 96 -> 0.61, 6 / 96 -> 0.54 (a few spilled registers cost less than the
-// extra wavefronts bring).
+// extra wavefronts bring); with the small survivor ring (six teams per compute unit), per
+// 1e9 values: 6 / 72 -> 1.02 ms, 6 / 96 -> 1.00, 6 / 128 -> 0.97, 7 / 120 -> 0.98.
 #ifndef QSGD_ENC_WAVES
 #define QSGD_ENC_WAVES 6
 #endif
 #ifndef QSGD_ENC_TEAMS
-#define QSGD_ENC_TEAMS 96u
+#define QSGD_ENC_TEAMS 128u
 #endif
 // Small-bucket fixed-width encoder: wavefronts per compute unit the grid may have.  A
 // persistent grid (32 per CU) measured 0.19 ms on c3, one pass per wavefront 0.15 ms.
@@ -94,6 +95,7 @@ struct EncodeArgs {
   uint32_t bper;        // buckets per team
   uint32_t dst_words;   // LDS words of the bucket-string image (even)
   uint32_t sub_words;   // LDS words of one wave's sub-stream (even)
+  uint32_t ring;        // records in a wavefront's survivor ring (Code_s): 256 or 128
   uint32_t* header;     // message header (16 words)
   uint32_t* table;      // nb+1 word offsets (Elias codes)
   uint32_t* staging;    // workspace: one region per team

@@ -109,6 +109,41 @@ def test_sparse_messages_counting_apply(K, d, s):
         run_case(w, norm=q.NORM_MAX)
 
 
+@pytest.mark.parametrize("s,d", [(10, 8192), (4, 8192), (7, 4096), (2, 2048)])
+def test_dense_chunks_inside_sparse_buckets(s, d):
+    """Parameters that promise few nonzero levels (8 s (s + sqrt(d)) <= d) with data that
+    breaks the promise: all of a bucket's mass in one or two chunks of 256 values, so that
+    a chunk brings up to 256 survivors.  A wavefront of the team encoder whose small
+    survivor ring cannot take such a chunk starts over with the direct coder."""
+    nb = 24
+    n = nb * d + d // 2
+    gen = torch.Generator().manual_seed(1234 + s)
+    g = torch.zeros(n)
+    for b in range(nb + 1):
+        m = min(d, n - b * d)
+        kind = b % 4
+        if kind == 3:                                   # an ordinary bucket
+            g[b * d:b * d + m] = torch.randn(m, generator=gen) * 1e-3
+            continue
+        chunks = torch.randperm(m // 256, generator=gen)[: 1 + kind].tolist()
+        for c in chunks:                                # full chunks of similar magnitudes
+            mag = 0.5 + torch.rand(256, generator=gen)
+            sign = torch.where(torch.rand(256, generator=gen) < 0.5, -1.0, 1.0)
+            g[b * d + c * 256: b * d + (c + 1) * 256] = mag * sign
+        g[b * d + (b * 37) % m] = 0.75                  # and a lone value somewhere
+    msgs_dev, msgs_host = [], []
+    for k in range(3):
+        P = q.Params(n=n, s=s, d=d, code=q.CODE_SPARSE, seed=77, stream_id=k, iteration=1)
+        status, words, msg = Device(P).encode(g.cuda())
+        assert status == 0
+        assert compare_encode(P, g.numpy(), words) == 0
+        msgs_dev.append(msg)
+        msgs_host.append(words)
+    P0 = q.Params(n=n, s=s, d=d, code=q.CODE_SPARSE, seed=77)
+    x = np.linspace(-1, 1, n, dtype=np.float32)
+    assert check_step(P0, msgs_dev, msgs_host, 0.1, x, 3) == 0
+
+
 def test_max_scaling():
     n = 512 * 64 + 12
     for code in (q.CODE_SPARSE, q.CODE_DENSE, q.CODE_FIXED):
