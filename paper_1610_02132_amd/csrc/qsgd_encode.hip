@@ -302,7 +302,8 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
       dst[j] = 0;
     }
     run += words;
-    __syncthreads();
+    // no barrier here: the image is next written after two barriers of the next bucket
+    // (scale exchange, sub-stream summaries), which every thread reaches after its zeroing
   }
   if (CODE != QSGD_CODE_FIXED && tid == 0) a.totals[blockIdx.x] = run;
 }
