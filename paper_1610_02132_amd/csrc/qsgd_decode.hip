@@ -515,7 +515,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
         }
         const uint32_t trips = __popcll(needy) >= 32 ? rec : kParse;   // dense data: no imbalance
         for (uint32_t np = 0; np < trips && have && qcnt < rec; ++np) {
-          if (pend_lev) {
+          if (kSparse || pend_lev) {   // (Code_s records always carry a level >= 1)
             queue[qidx((uint32_t)lane, (qhead + qcnt) & (rec - 1))] =
                 (qrec_t)((pend_pos - 1u) | (pend_neg << 13) | ((pend_lev - kLevBias) << 14));
             ++qcnt;
