@@ -368,6 +368,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   };
 
   // Reads the next record into pend_*; clears `have` at the end of the string.
+  bool bad = false;
   auto advance = [&]() {
     if (kSparse) {
       if (bitpos >= endbit) { have = false; return; }
@@ -388,10 +389,10 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       }
       pend_pos += gap;
       pend_lev = lev;
-      if (gap == 0 || lev == 0 || lev > s || pend_pos > m || bitpos > endbit) {
-        flag_corrupt(a.status);
-        have = false;
-      }
+      // a record that cannot be: remembered here, reported after the parse pass
+      const bool bad_rec = gap == 0 || lev == 0 || lev > s || pend_pos > m || bitpos > endbit;
+      bad = bad || bad_rec;
+      have = !bad_rec;
     } else {
       if (pend_pos >= m) { have = false; return; }
       uint32_t ll;
@@ -414,6 +415,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     nextw = slot[3];
   }
   if (open) { have = true; advance(); }
+  if (bad) { flag_corrupt(a.status); bad = false; }
 
   for (uint32_t j = lane; j < gw * winp; j += 64) acc[j] = 0.f;
   __syncthreads();
@@ -522,6 +524,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
           }
           advance();
         }
+        if (bad) { flag_corrupt(a.status); bad = false; }
       }
       if constexpr (KLOOP) {
         // Dense data: nearly every ring slot is due in every round, so the records are
