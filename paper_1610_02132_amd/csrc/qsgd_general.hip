@@ -594,18 +594,27 @@ __global__ __launch_bounds__(256) void k_gen_parse(DecodeArgs a, float* acc) {
 __global__ __launch_bounds__(256) void k_gen_parse_entries(DecodeArgs a, float* acc) {
   if (*a.status != 0) return;
   __shared__ uint32_t bad;
+  __shared__ StringRef refs[QSGD_MAX_PEERS];
   if (threadIdx.x == 0) bad = 0;
   const uint64_t b = blockIdx.x;
   const uint64_t base = b * (uint64_t)a.d;
   const uint64_t m = min((uint64_t)a.d, a.n - base);
   const bool sparse = a.code == QSGD_CODE_SPARSE;
   __syncthreads();
+  // the K strings are opened side by side (a chain of dependent reads each) before the
+  // messages take their turns
+  if (threadIdx.x < a.K) {
+    StringRef mine;
+    if (open_string(a, threadIdx.x, b, true, mine)) refs[threadIdx.x] = mine;
+    else bad = 1;
+  }
+  __syncthreads();
+  if (bad) {
+    if (threadIdx.x == 0) flag_corrupt(a.status);
+    return;
+  }
   for (uint32_t k = 0; k < a.K; ++k) {
-    StringRef sr;   // (every thread takes the same decisions here: uniform data)
-    if (!open_string(a, k, b, true, sr)) {
-      if (threadIdx.x == 0) flag_corrupt(a.status);
-      return;
-    }
+    const StringRef sr = refs[k];
     for (uint64_t r = threadIdx.x; r <= sr.ents; r += 256) {
       uint64_t bitpos = r ? sr.list[2 * (r - 1)] : 32;
       uint64_t pos = r ? sr.list[2 * (r - 1) + 1] : 0;
