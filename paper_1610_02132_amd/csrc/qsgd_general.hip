@@ -130,23 +130,32 @@ __global__ __launch_bounds__(256) void k_gen_scale(GenArgs a) {
     h[H_STATUS] = 0; h[H_ITER] = a.iteration;
   }
   if (b >= a.nb) return;
-  // four independent chains per lane: with thousands of segments in one bucket the
-  // dependent fp64 additions would otherwise set the pace
-  double acc4[4] = {0.0, 0.0, 0.0, 0.0};
-  uint64_t j = lane;
-  for (; j + 3 * kWave < a.spb; j += 4 * kWave) {
+  // sixteen independent chains per lane, their loads in flight together: with thousands of
+  // segments in one bucket the memory latency of each trip sets the pace
+  constexpr int kChains = 16;
+  double accs[kChains];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const double p = a.partial[b * a.spb + j + (uint64_t)t * kWave];
-      acc4[t] = a.norm_mode == 0 ? acc4[t] + p : fmax(acc4[t], p);
-    }
+  for (int t = 0; t < kChains; ++t) accs[t] = 0.0;
+  uint64_t j = lane;
+  for (; j + (kChains - 1) * kWave < a.spb; j += kChains * kWave) {
+    double p[kChains];
+#pragma unroll
+    for (int t = 0; t < kChains; ++t) p[t] = a.partial[b * a.spb + j + (uint64_t)t * kWave];
+#pragma unroll
+    for (int t = 0; t < kChains; ++t)
+      accs[t] = a.norm_mode == 0 ? accs[t] + p[t] : fmax(accs[t], p[t]);
   }
   for (; j < a.spb; j += kWave) {
     const double p = a.partial[b * a.spb + j];
-    acc4[0] = a.norm_mode == 0 ? acc4[0] + p : fmax(acc4[0], p);
+    accs[0] = a.norm_mode == 0 ? accs[0] + p : fmax(accs[0], p);
   }
-  const double acc = a.norm_mode == 0 ? (acc4[0] + acc4[1]) + (acc4[2] + acc4[3])
-                                      : fmax(fmax(acc4[0], acc4[1]), fmax(acc4[2], acc4[3]));
+#pragma unroll
+  for (int w = kChains / 2; w >= 1; w /= 2) {
+#pragma unroll
+    for (int t = 0; t < w; ++t)
+      accs[t] = a.norm_mode == 0 ? accs[t] + accs[t + w] : fmax(accs[t], accs[t + w]);
+  }
+  const double acc = accs[0];
   float scale;
   if (a.norm_mode == 0) scale = (float)sqrt(wave_sum_f64(acc));
   else scale = wave_max_f32((float)acc);
