@@ -74,7 +74,7 @@ __device__ __forceinline__ T block_incl_scan(T v, T identity, T* wave_tot, Op op
     const T t = __shfl_up(v, o, kWave);
     if (lane >= o) v = op(v, t);
   }
-  __syncthreads();
+  // (wave_tot is free here: every call ends with a barrier after its reads)
   if (lane == 63) wave_tot[wave] = v;
   __syncthreads();
   T pre = identity;
@@ -292,7 +292,7 @@ __global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
     unsigned long long prevg = i ? tmp[i - 1] : 0ull;
     prevg = prevg > c_max ? prevg : c_max;
     const unsigned long long chunk_max = tmp[1023];
-    __syncthreads();
+    // (tmp is written again only after the barriers of the next scan)
     const uint32_t prev_in_bucket = prevg > base ? (uint32_t)(prevg - base) : 0u;
     const uint32_t gap = (live && first && sparse) ? first - prev_in_bucket : 0u;
     const uint32_t glen = gap ? omega_length(gap) : 0u;
@@ -311,7 +311,6 @@ __global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
     tmp[i] = tb;
     __syncthreads();
     const unsigned long long tb_prev = i ? tmp[i - 1] : c_tb;
-    __syncthreads();
     const unsigned long long start = 32ull + before;
     const unsigned long long m_b = live ? min((unsigned long long)a.d, a.n - base) : 0ull;
     const bool listed = a.entries && live && j >= 1 && (unsigned long long)j * kSeg < m_b &&
@@ -325,7 +324,6 @@ __global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
     unsigned long long rank;  // listed segments of this bucket before this one
     if ((unsigned long long)j <= (unsigned long long)i) rank = e_excl - tmp[i - j];
     else rank = c_ents + e_excl;
-    __syncthreads();
     const bool is_end = live && j == a.spb - 1;
     const unsigned long long ents = rank + (listed ? 1ull : 0ull);  // at the end: of the bucket
     unsigned long long words = 0;
@@ -347,7 +345,7 @@ __global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
         a.table[b + 1] = off > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)off;
       }
     }
-    __syncthreads();
+    // (the carries were read at the top of this trip, several barriers ago)
     if (live && (i == 1023 || seg == a.nseg - 1)) {
       carry[0] = chunk_max > c_max ? chunk_max : c_max;
       carry[1] = is_end ? 0ull : before + tb;
