@@ -494,13 +494,20 @@ void k_encode_fixed_small(EncodeArgs a) {
 __global__ __launch_bounds__(1024) void k_encode_prefix(CompactArgs a, uint32_t teams) {
   __shared__ unsigned long long wave_tot[16];
   __shared__ unsigned long long carry;
+  constexpr uint32_t kPer = 8;   // totals per thread: kMaxTeams in one trip
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid == 0) carry = 0;
   __syncthreads();
-  for (uint32_t c0 = 0; c0 < teams; c0 += 1024) {
-    const uint32_t i = c0 + tid;
-    const unsigned long long v = i < teams ? a.totals[i] : 0ull;
-    unsigned long long incl = v;
+  for (uint32_t c0 = 0; c0 < teams; c0 += 1024 * kPer) {
+    const uint32_t i0 = c0 + (uint32_t)tid * kPer;
+    uint32_t v[kPer];
+    unsigned long long sum = 0;
+#pragma unroll
+    for (uint32_t t = 0; t < kPer; ++t) {
+      v[t] = i0 + t < teams ? a.totals[i0 + t] : 0u;
+      sum += v[t];
+    }
+    unsigned long long incl = sum;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
       const unsigned long long up = __shfl_up(incl, o, kWave);
@@ -510,7 +517,12 @@ __global__ __launch_bounds__(1024) void k_encode_prefix(CompactArgs a, uint32_t 
     __syncthreads();
     unsigned long long before = carry;
     for (int w = 0; w < wave; ++w) before += wave_tot[w];
-    if (i < teams) a.prefix[i] = before + incl - v;
+    unsigned long long run = before + incl - sum;
+#pragma unroll
+    for (uint32_t t = 0; t < kPer; ++t) {
+      if (i0 + t < teams) a.prefix[i0 + t] = run;
+      run += v[t];
+    }
     __syncthreads();
     if (tid == 1023) carry = before + incl;
     __syncthreads();
