@@ -66,14 +66,24 @@ __device__ __forceinline__ float4 load_quad_any(const float* __restrict__ g, uin
 }
 
 // Inclusive scans over a 1024-thread workgroup (16 wavefronts).
+// 64-bit value of the lane a DPP control names (0 where there is none).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ unsigned long long dpp_fetch_u64(unsigned long long v) {
+  const uint32_t lo = dpp_fetch<CTRL, ROW_MASK>((uint32_t)v);
+  const uint32_t hi = dpp_fetch<CTRL, ROW_MASK>((uint32_t)(v >> 32));
+  return ((unsigned long long)hi << 32) | lo;
+}
+
+// (the operations used here have 0 as their identity: sums and maxima of unsigned values)
 template <typename T, typename Op>
 __device__ __forceinline__ T block_incl_scan(T v, T identity, T* wave_tot, Op op) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const T t = __shfl_up(v, o, kWave);
-    if (lane >= o) v = op(v, t);
-  }
+  v = op(v, dpp_fetch_u64<kDppShr1, 0xf>(v));
+  v = op(v, dpp_fetch_u64<kDppShr2, 0xf>(v));
+  v = op(v, dpp_fetch_u64<kDppShr4, 0xf>(v));
+  v = op(v, dpp_fetch_u64<kDppShr8, 0xf>(v));
+  v = op(v, dpp_fetch_u64<kDppBcast15, 0xa>(v));
+  v = op(v, dpp_fetch_u64<kDppBcast31, 0xc>(v));
   // (wave_tot is free here: every call ends with a barrier after its reads)
   if (lane == 63) wave_tot[wave] = v;
   __syncthreads();
@@ -273,13 +283,22 @@ __global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
   }
   __syncthreads();
   const bool sparse = a.code == QSGD_CODE_SPARSE;
+  // the summaries of the next trip's segments are requested a trip ahead
+  uint32_t nfirst = 0, nlast = 0, nbits = 0;
+  if ((uint64_t)i < a.nseg) {
+    nfirst = a.seginfo[3 * (uint64_t)i]; nlast = a.seginfo[3 * (uint64_t)i + 1];
+    nbits = a.seginfo[3 * (uint64_t)i + 2];
+  }
   for (uint64_t c0 = 0; c0 < a.nseg; c0 += 1024) {
     const uint64_t seg = c0 + i;
     const bool live = seg < a.nseg;
-    uint64_t b = 0; uint32_t j = 0, first = 0, last = 0, bits = 0;
-    if (live) {
-      b = seg / a.spb; j = (uint32_t)(seg - b * a.spb);
-      first = a.seginfo[3 * seg]; last = a.seginfo[3 * seg + 1]; bits = a.seginfo[3 * seg + 2];
+    uint64_t b = 0; uint32_t j = 0;
+    const uint32_t first = nfirst, last = nlast, bits = nbits;   // (0 for segments past the end)
+    if (live) { b = seg / a.spb; j = (uint32_t)(seg - b * a.spb); }
+    nfirst = 0; nlast = 0; nbits = 0;
+    if (seg + 1024 < a.nseg) {
+      nfirst = a.seginfo[3 * (seg + 1024)]; nlast = a.seginfo[3 * (seg + 1024) + 1];
+      nbits = a.seginfo[3 * (seg + 1024) + 2];
     }
     const unsigned long long base = b * a.d;
     const unsigned long long c_max = carry[0], c_bits = carry[1], c_words = carry[2];
