@@ -304,6 +304,14 @@ int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* ms
       return QSGD_OK;
     }
     float* acc = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + kStatusBytes + kTotalsBytes);
+    // Long buckets of Code_s: a message has at most q = s (s + sqrt(d)) nonzero levels in
+    // expectation (Lemma 3.1 (iii)), so about K^2 q^2 / (2 d) coordinates are hit by two
+    // messages.  Where that is a few hundred at most, the K messages are read at once.
+    {
+      const double q = (double)g.s * ((double)g.s + std::sqrt((double)g.d));
+      a.together = (g.code == QSGD_CODE_SPARSE && g.d > kEntryMinD &&
+                    (double)K * K * q * q <= 512.0 * (double)g.d) ? 1u : 0u;
+    }
     if (launch_gen_zero(acc, g.n, blocks, st) != hipSuccess) return QSGD_ERR_HIP;
     if (launch_gen_parse(a, acc, g.d > kEntryMinD, st) != hipSuccess) return QSGD_ERR_HIP;
     if (launch_gen_apply(a, acc, blocks, st) != hipSuccess) return QSGD_ERR_HIP;

@@ -612,11 +612,48 @@ __global__ __launch_bounds__(256) void k_gen_parse(DecodeArgs a, float* acc) {
   }
 }
 
+// Opens the K strings of bucket b side by side (a chain of dependent reads each).
+// Returns false (every thread) if one of them is malformed.  Ends with a barrier.
+__device__ __forceinline__ bool open_strings(const DecodeArgs& a, uint64_t b, StringRef* refs,
+                                             uint32_t* bad) {
+  if (threadIdx.x < a.K) {
+    StringRef mine;
+    if (open_string(a, threadIdx.x, b, true, mine)) refs[threadIdx.x] = mine;
+    else *bad = 1;
+  }
+  __syncthreads();
+  return *bad == 0;
+}
+
+// The messages take their turns (a barrier in between), a thread per stretch between two
+// entry points: every coordinate receives its terms in message order.  Every stretch must
+// end exactly where the next one starts, at the position the list names.
+__device__ __forceinline__ bool parse_in_turns(const DecodeArgs& a, const StringRef* refs,
+                                               uint64_t m, float* out, uint32_t* bad) {
+  const bool sparse = a.code == QSGD_CODE_SPARSE;
+  for (uint32_t k = 0; k < a.K; ++k) {
+    const StringRef sr = refs[k];
+    for (uint64_t r = threadIdx.x; r <= sr.ents; r += blockDim.x) {
+      uint64_t bitpos = r ? sr.list[2 * (r - 1)] : 32;
+      uint64_t pos = r ? sr.list[2 * (r - 1) + 1] : 0;
+      const bool last_stretch = r == sr.ents;
+      const uint64_t stop = last_stretch ? sr.endbit : sr.list[2 * r];
+      bool ok = bitpos >= 32 && bitpos <= stop && stop <= sr.endbit && pos <= m;
+      ok = ok && parse_stretch(sr.str, sr.nwords, sparse, last_stretch && !sparse, stop, m, a.s,
+                               sr.scale, bitpos, pos, out);
+      // the stretch ends where the next one starts, at the position the list names
+      if (ok && !last_stretch) ok = bitpos == stop && pos == sr.list[2 * r + 1];
+      if (ok && last_stretch && !sparse) ok = pos == m && bitpos <= sr.endbit;
+      if (!ok) *bad = 1;
+    }
+    __syncthreads();   // message k is in before message k + 1 adds to the same coordinates
+    if (*bad) return false;
+  }
+  return true;
+}
+
 // Long buckets (d > kEntryMinD): the string is followed by a list of entry points, so a
-// workgroup reads one bucket with a thread per stretch between two entries, message
-// after message (a barrier in between): every coordinate receives its terms in message
-// order.  Every stretch must end exactly where the next one starts, at the position
-// the list names.
+// workgroup reads one bucket with a thread per stretch, message after message.
 __global__ __launch_bounds__(256) void k_gen_parse_entries(DecodeArgs a, float* acc) {
   if (*a.status != 0) return;
   __shared__ uint32_t bad;
@@ -625,40 +662,129 @@ __global__ __launch_bounds__(256) void k_gen_parse_entries(DecodeArgs a, float* 
   const uint64_t b = blockIdx.x;
   const uint64_t base = b * (uint64_t)a.d;
   const uint64_t m = min((uint64_t)a.d, a.n - base);
-  const bool sparse = a.code == QSGD_CODE_SPARSE;
   __syncthreads();
-  // the K strings are opened side by side (a chain of dependent reads each) before the
-  // messages take their turns
-  if (threadIdx.x < a.K) {
-    StringRef mine;
-    if (open_string(a, threadIdx.x, b, true, mine)) refs[threadIdx.x] = mine;
-    else bad = 1;
+  if (!open_strings(a, b, refs, &bad) || !parse_in_turns(a, refs, m, acc + base, &bad)) {
+    if (threadIdx.x == 0) flag_corrupt(a.status);
+  }
+}
+
+// Code_s records of one stretch, each handed to f(position (0-based), value).
+template <class F>
+__device__ __forceinline__ bool walk_stretch(const StringRef& sr, uint64_t stop, uint64_t m,
+                                             uint32_t s, uint64_t& bitpos, uint64_t& pos, F&& f) {
+  WordWindow win;
+  win.open(sr.str, sr.nwords, bitpos);
+  while (bitpos < stop) {
+    uint32_t gl, ll;
+    const uint32_t gap = omega_loop(win.peek(bitpos), gl);
+    if (gap == 0) return false;
+    const uint64_t w = win.peek(bitpos + gl);
+    const uint32_t lev = omega_loop(w << 1, ll);
+    bitpos += gl + 1u + ll;
+    pos += gap;
+    if (lev == 0 || lev > s || pos > m || bitpos > stop) return false;
+    const float mag = sr.scale * (float)lev;
+    f(pos - 1, (w >> 63) ? -mag : mag);
+  }
+  return true;
+}
+
+// Long buckets of sparse Code_s messages (the host expects few coordinates that several
+// messages hit): all K messages are read at the same time, a thread per (message, stretch).
+//   1  every record adds 1 to its coordinate's word of the accumulator (an integer count);
+//   2  the strings are read again: a record whose coordinate counts 1 stores its value
+//      (0 + v = v, the sum in message order); the others go to a list in LDS;
+//   3  a coordinate on the list is summed from 0 in message order by the thread that
+//      holds its record of the lowest message.
+// A list that overflows (the messages collide after all) makes the workgroup clear its
+// bucket and read the messages in turns instead.
+constexpr uint32_t kCollide = 1024;
+__global__ __launch_bounds__(1024) void k_gen_parse_together(DecodeArgs a, float* acc) {
+  if (*a.status != 0) return;
+  __shared__ uint32_t bad, nlist;
+  __shared__ StringRef refs[QSGD_MAX_PEERS];
+  __shared__ uint32_t first_item[QSGD_MAX_PEERS + 1];
+  __shared__ uint32_t lpos[kCollide];
+  __shared__ float lval[kCollide];
+  __shared__ uint8_t lk[kCollide];
+  if (threadIdx.x == 0) { bad = 0; nlist = 0; }
+  const uint64_t b = blockIdx.x;
+  const uint64_t base = b * (uint64_t)a.d;
+  const uint64_t m = min((uint64_t)a.d, a.n - base);
+  float* const out = acc + base;
+  uint32_t* const outu = reinterpret_cast<uint32_t*>(out);
+  __syncthreads();
+  if (!open_strings(a, b, refs, &bad)) {
+    if (threadIdx.x == 0) flag_corrupt(a.status);
+    return;
+  }
+  if (threadIdx.x == 0) {
+    uint64_t t = 0;
+    for (uint32_t k = 0; k < a.K; ++k) {
+      first_item[k] = (uint32_t)t;
+      t += refs[k].ents + 1;
+      if (t > 0x7FFFFFFFull) bad = 1;
+    }
+    first_item[a.K] = (uint32_t)t;
   }
   __syncthreads();
   if (bad) {
     if (threadIdx.x == 0) flag_corrupt(a.status);
     return;
   }
-  for (uint32_t k = 0; k < a.K; ++k) {
-    const StringRef sr = refs[k];
-    for (uint64_t r = threadIdx.x; r <= sr.ents; r += 256) {
+  const uint32_t items = first_item[a.K];
+  // one pass over this thread's stretches, every record handed to f(k, position, value)
+  auto pass = [&](auto&& f) {
+    for (uint32_t item = threadIdx.x; item < items; item += blockDim.x) {
+      uint32_t k = 0;
+      while (first_item[k + 1] <= item) ++k;
+      const StringRef sr = refs[k];
+      const uint64_t r = item - first_item[k];
       uint64_t bitpos = r ? sr.list[2 * (r - 1)] : 32;
       uint64_t pos = r ? sr.list[2 * (r - 1) + 1] : 0;
       const bool last_stretch = r == sr.ents;
       const uint64_t stop = last_stretch ? sr.endbit : sr.list[2 * r];
       bool ok = bitpos >= 32 && bitpos <= stop && stop <= sr.endbit && pos <= m;
-      ok = ok && parse_stretch(sr.str, sr.nwords, sparse, last_stretch && !sparse, stop, m, a.s,
-                               sr.scale, bitpos, pos, acc + base);
-      // the stretch ends where the next one starts, at the position the list names
+      ok = ok && walk_stretch(sr, stop, m, a.s, bitpos, pos,
+                              [&](uint64_t p, float v) { f(k, p, v); });
       if (ok && !last_stretch) ok = bitpos == stop && pos == sr.list[2 * r + 1];
-      if (ok && last_stretch && !sparse) ok = pos == m && bitpos <= sr.endbit;
       if (!ok) bad = 1;
     }
-    __syncthreads();   // message k is in before message k + 1 adds to the same coordinates
-    if (bad) {
-      if (threadIdx.x == 0) flag_corrupt(a.status);
-      return;
+  };
+  pass([&](uint32_t, uint64_t p, float) { atomicAdd(&outu[p], 1u); });
+  __syncthreads();
+  if (bad) {
+    if (threadIdx.x == 0) flag_corrupt(a.status);
+    return;
+  }
+  pass([&](uint32_t k, uint64_t p, float v) {
+    // (the counts were made by atomics in the L2: read them there, not from a line another
+    // workgroup of this compute unit may have cached while they were still changing)
+    if (__hip_atomic_load(&outu[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 1u) {
+      out[p] = v;
+    } else {
+      const uint32_t idx = atomicAdd(&nlist, 1u);
+      if (idx < kCollide) { lpos[idx] = (uint32_t)p; lval[idx] = v; lk[idx] = (uint8_t)k; }
     }
+  });
+  __syncthreads();
+  const uint32_t L = nlist;
+  if (L > kCollide) {
+    for (uint64_t p = threadIdx.x; p < m; p += blockDim.x) out[p] = 0.f;
+    __syncthreads();
+    if (!parse_in_turns(a, refs, m, out, &bad) && threadIdx.x == 0) flag_corrupt(a.status);
+    return;
+  }
+  for (uint32_t e = threadIdx.x; e < L; e += blockDim.x) {
+    const uint32_t p = lpos[e];
+    bool leader = true;
+    for (uint32_t j = 0; j < L; ++j) leader = leader && !(lpos[j] == p && lk[j] < lk[e]);
+    if (!leader) continue;
+    float sum = 0.f;
+    for (uint32_t k = lk[e]; k < a.K; ++k)
+      for (uint32_t j = 0; j < L; ++j)
+        if (lpos[j] == p && lk[j] == k) sum += lval[j];
+    out[p] = sum;
   }
 }
 
@@ -733,7 +859,9 @@ hipError_t launch_gen_zero(float* p, uint64_t n, uint32_t blocks, hipStream_t st
   return hipGetLastError();
 }
 hipError_t launch_gen_parse(const DecodeArgs& a, float* acc, bool entries, hipStream_t st) {
-  if (entries) {
+  if (entries && a.together) {   // (the host's choice: sparse messages that hardly collide)
+    hipLaunchKernelGGL(k_gen_parse_together, dim3(a.nb), dim3(1024), 0, st, a, acc);
+  } else if (entries) {
     hipLaunchKernelGGL(k_gen_parse_entries, dim3(a.nb), dim3(256), 0, st, a, acc);
   } else {
     hipLaunchKernelGGL(k_gen_parse, dim3((a.nb + 255) / 256), dim3(256), 0, st, a, acc);

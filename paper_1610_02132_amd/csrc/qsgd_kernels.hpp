@@ -148,6 +148,7 @@ struct DecodeArgs {
   uint32_t rec;          // record slots per string (message-by-message apply)
   uint32_t kloop;        // 1: records are applied message by message (dense messages)
   uint32_t q16;          // 1: 16-bit records (counting apply, s <= 4)
+  uint32_t together;     // 1: long buckets, all messages read at once (few shared coordinates)
   // fixed width
   uint32_t fixed_bits;
   uint32_t fixed_words_full;

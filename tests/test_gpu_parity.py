@@ -144,6 +144,39 @@ def test_dense_chunks_inside_sparse_buckets(s, d):
     assert check_step(P0, msgs_dev, msgs_host, 0.1, x, 3) == 0
 
 
+@pytest.mark.parametrize("same_gradient", [False, True])
+@pytest.mark.parametrize("nb", [1, 3])
+def test_long_sparse_buckets_read_all_messages_at_once(same_gradient, nb):
+    """Long buckets (d > 8192), s = 1, K = 16: the decoder reads the K messages at the same
+    time and sums coordinates that several messages hit from a list, in message order.
+    Spikes shared by all peers give coordinates with up to 16 terms; the same gradient for
+    every peer makes the messages collide so often that the list overflows and the
+    workgroup falls back to reading the messages in turns."""
+    d, K = 150_001, 16
+    n = nb * d - (7 if nb > 1 else 0)
+    gen = torch.Generator().manual_seed(99)
+    msgs_dev, msgs_host = [], []
+    g0 = torch.distributions.StudentT(3.0).sample((n,)) * 1e-3
+    for k in range(K):
+        if same_gradient:
+            g = g0.clone()
+        else:
+            g = torch.randn(n, generator=gen) * 1e-3
+            g[12345] = 0.5                       # every peer
+            g[n - 5] = -0.25 if k % 2 == 0 else 0.25
+            if k < 3:
+                g[777] = 0.125                   # three peers
+        P = q.Params(n=n, s=1, d=d, code=q.CODE_SPARSE, seed=3, stream_id=k, iteration=2)
+        status, words, msg = Device(P).encode(g.cuda())
+        assert status == 0
+        assert compare_encode(P, g.numpy(), words) == 0
+        msgs_dev.append(msg)
+        msgs_host.append(words)
+    P0 = q.Params(n=n, s=1, d=d, code=q.CODE_SPARSE, seed=3)
+    x = np.linspace(-1, 1, n, dtype=np.float32)
+    assert check_step(P0, msgs_dev, msgs_host, 0.1, x, K) == 0
+
+
 def test_max_scaling():
     n = 512 * 64 + 12
     for code in (q.CODE_SPARSE, q.CODE_DENSE, q.CODE_FIXED):
