@@ -108,7 +108,9 @@ void plan_general(const Geometry& g, GenPlan& pl) {
   pl.off_slots = o;
   if (g.code != QSGD_CODE_FIXED) o = align_up(o + 4 * pl.nseg * pl.sub_words, 256);
   pl.enc_bytes = o;
+  // decode: the dense accumulator, then a list per long bucket (see kCollide)
   pl.dec_bytes = g.code == QSGD_CODE_FIXED ? 0 : align_up(4 * g.n, 256);
+  if (g.code == QSGD_CODE_SPARSE && g.d > kEntryMinD) pl.dec_bytes += g.nb * (uint64_t)kCollideBytes;
 }
 
 int make_geometry(const qsgd_params* p, Geometry& g) {
@@ -313,7 +315,12 @@ int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* ms
                     (double)K * K * q * q <= 512.0 * (double)g.d) ? 1u : 0u;
     }
     if (launch_gen_zero(acc, g.n, blocks, st) != hipSuccess) return QSGD_ERR_HIP;
-    if (launch_gen_parse(a, acc, g.d > kEntryMinD, st) != hipSuccess) return QSGD_ERR_HIP;
+    if (a.together) {
+      uint8_t* lists = reinterpret_cast<uint8_t*>(acc) + align_up(4 * g.n, 256);
+      if (launch_gen_parse_together(a, acc, lists, st) != hipSuccess) return QSGD_ERR_HIP;
+    } else if (launch_gen_parse(a, acc, g.d > kEntryMinD, st) != hipSuccess) {
+      return QSGD_ERR_HIP;
+    }
     if (launch_gen_apply(a, acc, blocks, st) != hipSuccess) return QSGD_ERR_HIP;
     return QSGD_OK;
   }

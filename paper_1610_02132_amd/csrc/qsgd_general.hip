@@ -668,123 +668,180 @@ __global__ __launch_bounds__(256) void k_gen_parse_entries(DecodeArgs a, float* 
   }
 }
 
-// Code_s records of one stretch, each handed to f(position (0-based), value).
+// Code_s records of one stretch, handed to f eight at a time: f(positions (0-based; ~0 for
+// an unused slot), values), so that f can have its memory accesses in flight together.
+constexpr int kWalkBatch = 8;
 template <class F>
 __device__ __forceinline__ bool walk_stretch(const StringRef& sr, uint64_t stop, uint64_t m,
                                              uint32_t s, uint64_t& bitpos, uint64_t& pos, F&& f) {
   WordWindow win;
   win.open(sr.str, sr.nwords, bitpos);
-  while (bitpos < stop) {
-    uint32_t gl, ll;
-    const uint32_t gap = omega_loop(win.peek(bitpos), gl);
-    if (gap == 0) return false;
-    const uint64_t w = win.peek(bitpos + gl);
-    const uint32_t lev = omega_loop(w << 1, ll);
-    bitpos += gl + 1u + ll;
-    pos += gap;
-    if (lev == 0 || lev > s || pos > m || bitpos > stop) return false;
-    const float mag = sr.scale * (float)lev;
-    f(pos - 1, (w >> 63) ? -mag : mag);
+  for (;;) {
+    uint64_t where[kWalkBatch];
+    float what[kWalkBatch];
+    bool done = false;
+#pragma unroll
+    for (int t = 0; t < kWalkBatch; ++t) {
+      where[t] = ~0ull;
+      what[t] = 0.f;
+      if (done) continue;
+      if (bitpos >= stop) { done = true; continue; }
+      uint32_t gl, ll;
+      const uint32_t gap = omega_loop(win.peek(bitpos), gl);
+      if (gap == 0) return false;
+      const uint64_t w = win.peek(bitpos + gl);
+      const uint32_t lev = omega_loop(w << 1, ll);
+      bitpos += gl + 1u + ll;
+      pos += gap;
+      if (lev == 0 || lev > s || pos > m || bitpos > stop) return false;
+      const float mag = sr.scale * (float)lev;
+      where[t] = pos - 1;
+      what[t] = (w >> 63) ? -mag : mag;
+    }
+    f(where, what);
+    if (done) return true;
   }
-  return true;
 }
 
 // Long buckets of sparse Code_s messages (the host expects few coordinates that several
-// messages hit): all K messages are read at the same time, a thread per (message, stretch).
-//   1  every record adds 1 to its coordinate's word of the accumulator (an integer count);
-//   2  the strings are read again: a record whose coordinate counts 1 stores its value
-//      (0 + v = v, the sum in message order); the others go to a list in LDS;
-//   3  a coordinate on the list is summed from 0 in message order by the thread that
-//      holds its record of the lowest message.
-// A list that overflows (the messages collide after all) makes the workgroup clear its
-// bucket and read the messages in turns instead.
-constexpr uint32_t kCollide = 1024;
-__global__ __launch_bounds__(1024) void k_gen_parse_together(DecodeArgs a, float* acc) {
+// messages hit): all K messages are read at the same time, a workgroup per (bucket,
+// message) and a thread per stretch, in three kernels:
+//   count    every record adds 1 to its coordinate's word of the accumulator (an integer);
+//   store    the strings are read again: a record whose coordinate counts 1 stores its
+//            value (0 + v = v, the sum in message order); the others go to the bucket's
+//            list in the workspace;
+//   resolve  a coordinate on the list is summed from 0 in message order by the thread that
+//            holds its record of the lowest message.  A list that overflowed (the messages
+//            collide after all) makes the bucket's workgroup clear the bucket and read the
+//            messages in turns.
+struct CollideList {
+  uint32_t* count;
+  uint32_t* pos;
+  float* val;
+  uint32_t* msg;
+};
+__device__ __forceinline__ CollideList collide_list(uint8_t* lists, uint64_t b) {
+  uint8_t* const base = lists + b * (uint64_t)kCollideBytes;
+  CollideList l;
+  l.count = reinterpret_cast<uint32_t*>(base);
+  l.pos = reinterpret_cast<uint32_t*>(base + 256);
+  l.val = reinterpret_cast<float*>(base + 256 + 4 * kCollide);
+  l.msg = reinterpret_cast<uint32_t*>(base + 256 + 8 * kCollide);
+  return l;
+}
+
+__global__ __launch_bounds__(256) void k_gen_zero_lists(uint8_t* lists, uint64_t nb) {
+  const uint64_t b = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (b < nb) *collide_list(lists, b).count = 0;
+}
+
+// STORE false: the counting pass; true: the storing pass.
+template <bool STORE>
+__global__ __launch_bounds__(256) void k_gen_walk(DecodeArgs a, float* acc, uint8_t* lists) {
   if (*a.status != 0) return;
-  __shared__ uint32_t bad, nlist;
-  __shared__ StringRef refs[QSGD_MAX_PEERS];
-  __shared__ uint32_t first_item[QSGD_MAX_PEERS + 1];
-  __shared__ uint32_t lpos[kCollide];
-  __shared__ float lval[kCollide];
-  __shared__ uint8_t lk[kCollide];
-  if (threadIdx.x == 0) { bad = 0; nlist = 0; }
+  __shared__ StringRef ref;
+  __shared__ uint32_t bad;
   const uint64_t b = blockIdx.x;
+  const uint32_t k = blockIdx.y;
+  if (threadIdx.x == 0) {
+    StringRef mine;
+    bad = open_string(a, k, b, true, mine) ? 0u : 1u;
+    if (!bad) ref = mine;
+  }
+  __syncthreads();
+  if (bad) {
+    if (threadIdx.x == 0) flag_corrupt(a.status);
+    return;
+  }
+  const StringRef sr = ref;
   const uint64_t base = b * (uint64_t)a.d;
   const uint64_t m = min((uint64_t)a.d, a.n - base);
   float* const out = acc + base;
   uint32_t* const outu = reinterpret_cast<uint32_t*>(out);
-  __syncthreads();
-  if (!open_strings(a, b, refs, &bad)) {
-    if (threadIdx.x == 0) flag_corrupt(a.status);
-    return;
+  const CollideList cl = collide_list(lists, b);
+  for (uint64_t r = threadIdx.x; r <= sr.ents; r += blockDim.x) {
+    uint64_t bitpos = r ? sr.list[2 * (r - 1)] : 32;
+    uint64_t pos = r ? sr.list[2 * (r - 1) + 1] : 0;
+    const bool last_stretch = r == sr.ents;
+    const uint64_t stop = last_stretch ? sr.endbit : sr.list[2 * r];
+    bool ok = bitpos >= 32 && bitpos <= stop && stop <= sr.endbit && pos <= m;
+    ok = ok && walk_stretch(sr, stop, m, a.s, bitpos, pos,
+                            [&](const uint64_t (&p)[kWalkBatch], const float (&v)[kWalkBatch]) {
+      if (!STORE) {
+#pragma unroll
+        for (int t = 0; t < kWalkBatch; ++t)
+          if (p[t] != ~0ull) atomicAdd(&outu[p[t]], 1u);
+      } else {
+        uint32_t c[kWalkBatch];
+#pragma unroll
+        for (int t = 0; t < kWalkBatch; ++t) c[t] = p[t] != ~0ull ? outu[p[t]] : 0u;
+#pragma unroll
+        for (int t = 0; t < kWalkBatch; ++t) {
+          if (p[t] == ~0ull) continue;
+          if (c[t] == 1u) {   // (only this record names the coordinate: nobody else touches it)
+            out[p[t]] = v[t];
+          } else {
+            const uint32_t idx = atomicAdd(cl.count, 1u);
+            if (idx < kCollide) {
+              cl.pos[idx] = (uint32_t)p[t]; cl.val[idx] = v[t]; cl.msg[idx] = k;
+            }
+          }
+        }
+      }
+    });
+    // the stretch ends where the next one starts, at the position the list names
+    if (ok && !last_stretch) ok = bitpos == stop && pos == sr.list[2 * r + 1];
+    if (!ok) flag_corrupt(a.status);
   }
-  if (threadIdx.x == 0) {
-    uint64_t t = 0;
-    for (uint32_t k = 0; k < a.K; ++k) {
-      first_item[k] = (uint32_t)t;
-      t += refs[k].ents + 1;
-      if (t > 0x7FFFFFFFull) bad = 1;
-    }
-    first_item[a.K] = (uint32_t)t;
-  }
+}
+
+__global__ __launch_bounds__(1024) void k_gen_resolve(DecodeArgs a, float* acc, uint8_t* lists) {
+  if (*a.status != 0) return;
+  __shared__ uint32_t bad;
+  __shared__ StringRef refs[QSGD_MAX_PEERS];
+  __shared__ uint32_t lpos[kCollide];
+  __shared__ float lval[kCollide];
+  __shared__ uint8_t lk[kCollide];
+  const uint64_t b = blockIdx.x;
+  const uint64_t base = b * (uint64_t)a.d;
+  const uint64_t m = min((uint64_t)a.d, a.n - base);
+  float* const out = acc + base;
+  const CollideList cl = collide_list(lists, b);
+  const uint32_t L = *cl.count;
+  if (threadIdx.x == 0) bad = 0;
   __syncthreads();
-  if (bad) {
-    if (threadIdx.x == 0) flag_corrupt(a.status);
-    return;
-  }
-  const uint32_t items = first_item[a.K];
-  // one pass over this thread's stretches, every record handed to f(k, position, value)
-  auto pass = [&](auto&& f) {
-    for (uint32_t item = threadIdx.x; item < items; item += blockDim.x) {
-      uint32_t k = 0;
-      while (first_item[k + 1] <= item) ++k;
-      const StringRef sr = refs[k];
-      const uint64_t r = item - first_item[k];
-      uint64_t bitpos = r ? sr.list[2 * (r - 1)] : 32;
-      uint64_t pos = r ? sr.list[2 * (r - 1) + 1] : 0;
-      const bool last_stretch = r == sr.ents;
-      const uint64_t stop = last_stretch ? sr.endbit : sr.list[2 * r];
-      bool ok = bitpos >= 32 && bitpos <= stop && stop <= sr.endbit && pos <= m;
-      ok = ok && walk_stretch(sr, stop, m, a.s, bitpos, pos,
-                              [&](uint64_t p, float v) { f(k, p, v); });
-      if (ok && !last_stretch) ok = bitpos == stop && pos == sr.list[2 * r + 1];
-      if (!ok) bad = 1;
-    }
-  };
-  pass([&](uint32_t, uint64_t p, float) { atomicAdd(&outu[p], 1u); });
-  __syncthreads();
-  if (bad) {
-    if (threadIdx.x == 0) flag_corrupt(a.status);
-    return;
-  }
-  pass([&](uint32_t k, uint64_t p, float v) {
-    // (the counts were made by atomics in the L2: read them there, not from a line another
-    // workgroup of this compute unit may have cached while they were still changing)
-    if (__hip_atomic_load(&outu[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 1u) {
-      out[p] = v;
-    } else {
-      const uint32_t idx = atomicAdd(&nlist, 1u);
-      if (idx < kCollide) { lpos[idx] = (uint32_t)p; lval[idx] = v; lk[idx] = (uint8_t)k; }
-    }
-  });
-  __syncthreads();
-  const uint32_t L = nlist;
   if (L > kCollide) {
     for (uint64_t p = threadIdx.x; p < m; p += blockDim.x) out[p] = 0.f;
     __syncthreads();
-    if (!parse_in_turns(a, refs, m, out, &bad) && threadIdx.x == 0) flag_corrupt(a.status);
+    if (!open_strings(a, b, refs, &bad) || !parse_in_turns(a, refs, m, out, &bad)) {
+      if (threadIdx.x == 0) flag_corrupt(a.status);
+    }
     return;
   }
   for (uint32_t e = threadIdx.x; e < L; e += blockDim.x) {
+    lpos[e] = cl.pos[e]; lval[e] = cl.val[e]; lk[e] = (uint8_t)cl.msg[e];
+  }
+  __syncthreads();
+  // (a message names a coordinate at most once: the terms of p are found in message order
+  // by looking for the lowest message above the last one, terms + 1 scans of the list)
+  for (uint32_t e = threadIdx.x; e < L; e += blockDim.x) {
     const uint32_t p = lpos[e];
-    bool leader = true;
-    for (uint32_t j = 0; j < L; ++j) leader = leader && !(lpos[j] == p && lk[j] < lk[e]);
-    if (!leader) continue;
     float sum = 0.f;
-    for (uint32_t k = lk[e]; k < a.K; ++k)
-      for (uint32_t j = 0; j < L; ++j)
-        if (lpos[j] == p && lk[j] == k) sum += lval[j];
-    out[p] = sum;
+    int last = -1;
+    for (;;) {
+      uint32_t best = 0xFFFFFFFFu;
+      float bestv = 0.f;
+#pragma unroll 4
+      for (uint32_t j = 0; j < L; ++j) {
+        const uint32_t kj = lk[j];
+        if (lpos[j] == p && (int)kj > last && kj < best) { best = kj; bestv = lval[j]; }
+      }
+      if (best == 0xFFFFFFFFu) break;
+      if (last < 0 && best != lk[e]) break;   // another thread holds the lowest message: its job
+      sum += bestv;
+      last = (int)best;
+    }
+    if (last >= 0) out[p] = sum;
   }
 }
 
@@ -859,13 +916,22 @@ hipError_t launch_gen_zero(float* p, uint64_t n, uint32_t blocks, hipStream_t st
   return hipGetLastError();
 }
 hipError_t launch_gen_parse(const DecodeArgs& a, float* acc, bool entries, hipStream_t st) {
-  if (entries && a.together) {   // (the host's choice: sparse messages that hardly collide)
-    hipLaunchKernelGGL(k_gen_parse_together, dim3(a.nb), dim3(1024), 0, st, a, acc);
-  } else if (entries) {
+  if (entries) {
     hipLaunchKernelGGL(k_gen_parse_entries, dim3(a.nb), dim3(256), 0, st, a, acc);
   } else {
     hipLaunchKernelGGL(k_gen_parse, dim3((a.nb + 255) / 256), dim3(256), 0, st, a, acc);
   }
+  return hipGetLastError();
+}
+// lists: a.nb x kCollideBytes of workspace behind the accumulator.
+hipError_t launch_gen_parse_together(const DecodeArgs& a, float* acc, uint8_t* lists,
+                                     hipStream_t st) {
+  hipLaunchKernelGGL(k_gen_zero_lists, dim3((a.nb + 255) / 256), dim3(256), 0, st, lists,
+                     (uint64_t)a.nb);
+  const dim3 grid(a.nb, a.K);
+  hipLaunchKernelGGL((k_gen_walk<false>), grid, dim3(256), 0, st, a, acc, lists);
+  hipLaunchKernelGGL((k_gen_walk<true>), grid, dim3(256), 0, st, a, acc, lists);
+  hipLaunchKernelGGL(k_gen_resolve, dim3(a.nb), dim3(1024), 0, st, a, acc, lists);
   return hipGetLastError();
 }
 hipError_t launch_gen_apply(const DecodeArgs& a, const float* acc, uint32_t blocks, hipStream_t st) {

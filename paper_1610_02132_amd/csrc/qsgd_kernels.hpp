@@ -233,6 +233,12 @@ hipError_t launch_gen_fill(const GenArgs& a, uint32_t blocks, hipStream_t st);
 hipError_t launch_gen_place(const GenArgs& a, hipStream_t st);
 hipError_t launch_gen_zero(float* p, uint64_t n, uint32_t blocks, hipStream_t st);
 hipError_t launch_gen_parse(const DecodeArgs& a, float* acc, bool entries, hipStream_t st);
+// Long buckets read with all messages at once: records at coordinates that several
+// messages hit go to a list per bucket (a count, then kCollide x (position, value, message)).
+constexpr uint32_t kCollide = 1024;
+constexpr uint32_t kCollideBytes = 256 + 12 * kCollide;
+hipError_t launch_gen_parse_together(const DecodeArgs& a, float* acc, uint8_t* lists,
+                                     hipStream_t st);
 hipError_t launch_gen_apply(const DecodeArgs& a, const float* acc, uint32_t blocks, hipStream_t st);
 hipError_t launch_gen_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t st);
 
