@@ -270,10 +270,15 @@ __global__ __launch_bounds__(64) void k_gen_encode(GenArgs a) {
   for (uint32_t j = lane; j < nw; j += kWave) slot[j] = sub[j];
 }
 
-// One workgroup of 1024 threads walks all segments in order.
+// One workgroup of 1024 threads walks all segments in order, kScanPer consecutive segments
+// per thread and trip: a thread scans its own segments one after the other and the
+// workgroup scans the threads' totals.
+constexpr int kScanPer = 4;
+constexpr uint32_t kScanTrip = 1024 * kScanPer;
 __global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
   __shared__ unsigned long long wave_tot[16];
-  __shared__ unsigned long long tmp[1024];
+  __shared__ unsigned long long tmp[kScanTrip];   // one value per segment of the trip
+  __shared__ unsigned long long tot[1024];        // one value per thread
   __shared__ unsigned long long carry[5];  // max global position, bits in open bucket, words,
                                            // bits of the last segment, entries in open bucket
   const int i = threadIdx.x;
@@ -283,94 +288,132 @@ __global__ __launch_bounds__(1024) void k_gen_scan(GenArgs a) {
   }
   __syncthreads();
   const bool sparse = a.code == QSGD_CODE_SPARSE;
-  // the summaries of the next trip's segments are requested a trip ahead
-  uint32_t nfirst = 0, nlast = 0, nbits = 0;
-  if ((uint64_t)i < a.nseg) {
-    nfirst = a.seginfo[3 * (uint64_t)i]; nlast = a.seginfo[3 * (uint64_t)i + 1];
-    nbits = a.seginfo[3 * (uint64_t)i + 2];
-  }
-  for (uint64_t c0 = 0; c0 < a.nseg; c0 += 1024) {
-    const uint64_t seg = c0 + i;
-    const bool live = seg < a.nseg;
-    uint64_t b = 0; uint32_t j = 0;
-    const uint32_t first = nfirst, last = nlast, bits = nbits;   // (0 for segments past the end)
-    if (live) { b = seg / a.spb; j = (uint32_t)(seg - b * a.spb); }
-    nfirst = 0; nlast = 0; nbits = 0;
-    if (seg + 1024 < a.nseg) {
-      nfirst = a.seginfo[3 * (seg + 1024)]; nlast = a.seginfo[3 * (seg + 1024) + 1];
-      nbits = a.seginfo[3 * (seg + 1024) + 2];
+  for (uint64_t c0 = 0; c0 < a.nseg; c0 += kScanTrip) {
+    uint64_t seg[kScanPer], b[kScanPer];
+    uint32_t idx[kScanPer], j[kScanPer], first[kScanPer], last[kScanPer], bits[kScanPer];
+    bool live[kScanPer];
+    unsigned long long base[kScanPer];
+#pragma unroll
+    for (int t = 0; t < kScanPer; ++t) {
+      idx[t] = (uint32_t)i * kScanPer + t;
+      seg[t] = c0 + idx[t];
+      live[t] = seg[t] < a.nseg;
+      b[t] = 0; j[t] = 0; first[t] = 0; last[t] = 0; bits[t] = 0;
+      if (live[t]) {
+        b[t] = seg[t] / a.spb; j[t] = (uint32_t)(seg[t] - b[t] * a.spb);
+        first[t] = a.seginfo[3 * seg[t]]; last[t] = a.seginfo[3 * seg[t] + 1];
+        bits[t] = a.seginfo[3 * seg[t] + 2];
+      }
+      base[t] = b[t] * a.d;
     }
-    const unsigned long long base = b * a.d;
     const unsigned long long c_max = carry[0], c_bits = carry[1], c_words = carry[2];
     const unsigned long long c_tb = carry[3], c_ents = carry[4];
-    // which nonzero precedes this segment's first one
-    const unsigned long long lastg = (live && first) ? base + last : 0ull;
-    const unsigned long long m_incl = block_incl_scan<unsigned long long>(lastg, 0ull, wave_tot, OpMax());
-    tmp[i] = m_incl;
+    // which nonzero precedes each segment's first one: prefix maximum of the last positions
+    unsigned long long m_loc[kScanPer];
+#pragma unroll
+    for (int t = 0; t < kScanPer; ++t) {
+      const unsigned long long lastg = (live[t] && first[t]) ? base[t] + last[t] : 0ull;
+      m_loc[t] = t ? (m_loc[t - 1] > lastg ? m_loc[t - 1] : lastg) : lastg;
+    }
+    tot[i] = block_incl_scan<unsigned long long>(m_loc[kScanPer - 1], 0ull, wave_tot, OpMax());
     __syncthreads();
-    unsigned long long prevg = i ? tmp[i - 1] : 0ull;
-    prevg = prevg > c_max ? prevg : c_max;
-    const unsigned long long chunk_max = tmp[1023];
-    // (tmp is written again only after the barriers of the next scan)
-    const uint32_t prev_in_bucket = prevg > base ? (uint32_t)(prevg - base) : 0u;
-    const uint32_t gap = (live && first && sparse) ? first - prev_in_bucket : 0u;
-    const uint32_t glen = gap ? omega_length(gap) : 0u;
-    const unsigned long long tb = (unsigned long long)glen + bits;
-    // bit offset of the segment inside its bucket string
-    const unsigned long long s_incl = block_incl_scan<unsigned long long>(tb, 0ull, wave_tot, OpSum());
-    const unsigned long long s_excl = s_incl - tb;
-    tmp[i] = s_excl;
+    const unsigned long long m_before = i ? tot[i - 1] : 0ull;   // threads before this one
+    const unsigned long long chunk_max = tot[1023];
+    uint32_t prev_in_bucket[kScanPer], gap[kScanPer];
+    unsigned long long tb[kScanPer], s_loc[kScanPer];
+#pragma unroll
+    for (int t = 0; t < kScanPer; ++t) {
+      unsigned long long prevg = t ? (m_before > m_loc[t - 1] ? m_before : m_loc[t - 1]) : m_before;
+      prevg = prevg > c_max ? prevg : c_max;
+      prev_in_bucket[t] = prevg > base[t] ? (uint32_t)(prevg - base[t]) : 0u;
+      gap[t] = (live[t] && first[t] && sparse) ? first[t] - prev_in_bucket[t] : 0u;
+      const uint32_t glen = gap[t] ? omega_length(gap[t]) : 0u;
+      tb[t] = (unsigned long long)glen + bits[t];
+      s_loc[t] = (t ? s_loc[t - 1] : 0ull) + tb[t];
+    }
+    // bit offset of each segment inside its bucket string
+    const unsigned long long s_tot =
+        block_incl_scan<unsigned long long>(s_loc[kScanPer - 1], 0ull, wave_tot, OpSum());
+    unsigned long long s_excl[kScanPer];
+#pragma unroll
+    for (int t = 0; t < kScanPer; ++t) {
+      s_excl[t] = s_tot - s_loc[kScanPer - 1] + s_loc[t] - tb[t];
+      tmp[idx[t]] = s_excl[t];
+    }
+    tot[i] = tb[kScanPer - 1];   // (tot was last read before the scan's barriers)
     __syncthreads();
-    unsigned long long before;  // bits of this bucket's records before this segment
-    if ((unsigned long long)j <= (unsigned long long)i) before = s_excl - tmp[i - j];
-    else before = c_bits + s_excl;
+    unsigned long long before[kScanPer], tb_prev[kScanPer];
+#pragma unroll
+    for (int t = 0; t < kScanPer; ++t) {
+      // bits of this bucket's records before this segment
+      if (j[t] <= idx[t]) before[t] = s_excl[t] - tmp[idx[t] - j[t]];
+      else before[t] = c_bits + s_excl[t];
+      tb_prev[t] = t ? tb[t - 1] : (i ? tot[i - 1] : c_tb);
+    }
     __syncthreads();
     // entry list of long buckets: segment j >= 1 is listed iff its bit offset lies in a
     // later block of kEntryBits bits than the offset of segment j - 1
-    tmp[i] = tb;
-    __syncthreads();
-    const unsigned long long tb_prev = i ? tmp[i - 1] : c_tb;
-    const unsigned long long start = 32ull + before;
-    const unsigned long long m_b = live ? min((unsigned long long)a.d, a.n - base) : 0ull;
-    const bool listed = a.entries && live && j >= 1 && (unsigned long long)j * kSeg < m_b &&
-                        (start / kEntryBits) > ((start - tb_prev) / kEntryBits) &&
-                        start < (1ull << 32);
-    const unsigned long long e_incl =
-        block_incl_scan<unsigned long long>(listed ? 1ull : 0ull, 0ull, wave_tot, OpSum());
-    const unsigned long long e_excl = e_incl - (listed ? 1ull : 0ull);
-    tmp[i] = e_excl;
-    __syncthreads();
-    unsigned long long rank;  // listed segments of this bucket before this one
-    if ((unsigned long long)j <= (unsigned long long)i) rank = e_excl - tmp[i - j];
-    else rank = c_ents + e_excl;
-    const bool is_end = live && j == a.spb - 1;
-    const unsigned long long ents = rank + (listed ? 1ull : 0ull);  // at the end: of the bucket
-    unsigned long long words = 0;
-    if (is_end) {
-      words = (32ull + before + tb + (sparse ? 1ull : 0ull) + 31ull) >> 5;
-      if (a.entries) words += 2ull * ents + 1ull;
+    bool listed[kScanPer];
+    unsigned long long e_loc[kScanPer];
+#pragma unroll
+    for (int t = 0; t < kScanPer; ++t) {
+      const unsigned long long start = 32ull + before[t];
+      const unsigned long long m_b = live[t] ? min((unsigned long long)a.d, a.n - base[t]) : 0ull;
+      listed[t] = a.entries && live[t] && j[t] >= 1 && (unsigned long long)j[t] * kSeg < m_b &&
+                  (start / kEntryBits) > ((start - tb_prev[t]) / kEntryBits) &&
+                  start < (1ull << 32);
+      e_loc[t] = (t ? e_loc[t - 1] : 0ull) + (listed[t] ? 1ull : 0ull);
     }
-    const unsigned long long w_incl = block_incl_scan<unsigned long long>(words, 0ull, wave_tot, OpSum());
-    if (live) {
-      a.segstart[seg] = 32ull + before;
-      a.seggap[seg] = gap;
+    const unsigned long long e_tot =
+        block_incl_scan<unsigned long long>(e_loc[kScanPer - 1], 0ull, wave_tot, OpSum());
+    unsigned long long e_excl[kScanPer];
+#pragma unroll
+    for (int t = 0; t < kScanPer; ++t) {
+      e_excl[t] = e_tot - e_loc[kScanPer - 1] + e_loc[t] - (listed[t] ? 1ull : 0ull);
+      tmp[idx[t]] = e_excl[t];
+    }
+    __syncthreads();
+    unsigned long long rank[kScanPer], ents[kScanPer], w_loc[kScanPer];
+    bool is_end[kScanPer];
+#pragma unroll
+    for (int t = 0; t < kScanPer; ++t) {
+      // listed segments of this bucket before this one
+      if (j[t] <= idx[t]) rank[t] = e_excl[t] - tmp[idx[t] - j[t]];
+      else rank[t] = c_ents + e_excl[t];
+      is_end[t] = live[t] && j[t] == a.spb - 1;
+      ents[t] = rank[t] + (listed[t] ? 1ull : 0ull);  // at the end: of the bucket
+      unsigned long long words = 0;
+      if (is_end[t]) {
+        words = (32ull + before[t] + tb[t] + (sparse ? 1ull : 0ull) + 31ull) >> 5;
+        if (a.entries) words += 2ull * ents[t] + 1ull;
+      }
+      w_loc[t] = (t ? w_loc[t - 1] : 0ull) + words;
+    }
+    const unsigned long long w_tot =
+        block_incl_scan<unsigned long long>(w_loc[kScanPer - 1], 0ull, wave_tot, OpSum());
+#pragma unroll
+    for (int t = 0; t < kScanPer; ++t) {
+      if (!live[t]) continue;
+      const unsigned long long w_incl = w_tot - w_loc[kScanPer - 1] + w_loc[t];
+      a.segstart[seg[t]] = 32ull + before[t];
+      a.seggap[seg[t]] = gap[t];
       if (a.entries) {
-        a.segrank[seg] = listed ? (uint32_t)rank : 0xFFFFFFFFu;
-        a.segprev[seg] = sparse ? prev_in_bucket : j * kSeg;
-        if (is_end) a.bents[b] = (uint32_t)ents;
+        a.segrank[seg[t]] = listed[t] ? (uint32_t)rank[t] : 0xFFFFFFFFu;
+        a.segprev[seg[t]] = sparse ? prev_in_bucket[t] : j[t] * kSeg;
+        if (is_end[t]) a.bents[b[t]] = (uint32_t)ents[t];
       }
-      if (is_end) {
+      if (is_end[t]) {
         const unsigned long long off = c_words + w_incl;
-        a.table[b + 1] = off > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)off;
+        a.table[b[t] + 1] = off > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)off;
       }
-    }
-    // (the carries were read at the top of this trip, several barriers ago)
-    if (live && (i == 1023 || seg == a.nseg - 1)) {
-      carry[0] = chunk_max > c_max ? chunk_max : c_max;
-      carry[1] = is_end ? 0ull : before + tb;
-      carry[2] = c_words + w_incl;
-      carry[3] = tb;
-      carry[4] = is_end ? 0ull : ents;
+      // (the carries were read at the top of this trip, several barriers ago)
+      if (idx[t] == kScanTrip - 1 || seg[t] == a.nseg - 1) {
+        carry[0] = chunk_max > c_max ? chunk_max : c_max;
+        carry[1] = is_end[t] ? 0ull : before[t] + tb[t];
+        carry[2] = c_words + w_incl;
+        carry[3] = tb[t];
+        carry[4] = is_end[t] ? 0ull : ents[t];
+      }
     }
     __syncthreads();
   }
