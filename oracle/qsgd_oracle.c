@@ -822,6 +822,54 @@ int qo_sgd_step(const void *const *msgs, const size_t *bytes, uint32_t K, float 
   return QO_OK;
 }
 
+/* The same step restricted to the buckets [bucket_begin, bucket_begin + bucket_count):
+ * buckets are quantized and coded independently (Sec. 4), so the update of the
+ * coordinates of a run of buckets only needs those buckets' strings.  x points at the
+ * first coordinate of bucket `bucket_begin`.  Same arithmetic as qo_sgd_step, one
+ * bucket at a time. */
+int qo_sgd_step_buckets(const void *const *msgs, const size_t *bytes, uint32_t K, float eta,
+                        float *x, uint64_t bucket_begin, uint64_t bucket_count) {
+  if (K < 1 || !msgs || !bytes || !x) return QO_ERR_INVALID_ARG;
+  view *vs = (view *)calloc(K, sizeof(view));
+  if (!vs) return QO_ERR_INVALID_ARG;
+  int rc = QO_OK;
+  for (uint32_t k = 0; k < K && rc == QO_OK; ++k) {
+    rc = open_msg(msgs[k], bytes[k], &vs[k]);
+    if (rc == QO_OK && (vs[k].p.n != vs[0].p.n || vs[k].d != vs[0].d)) rc = QO_ERR_INVALID_ARG;
+  }
+  if (rc == QO_OK && (bucket_begin > vs[0].nb || bucket_count > vs[0].nb - bucket_begin))
+    rc = QO_ERR_INVALID_ARG;
+  if (rc) { free(vs); return rc; }
+  uint64_t d = vs[0].d ? vs[0].d : 1;
+  uint32_t *lv = (uint32_t *)malloc(d * sizeof(uint32_t));
+  uint8_t *ng = (uint8_t *)malloc(d);
+  float *dec = (float *)malloc((size_t)K * d * sizeof(float));
+  if (!lv || !ng || !dec) { free(lv); free(ng); free(dec); free(vs); return QO_ERR_INVALID_ARG; }
+  float c = eta / (float)K;
+  for (uint64_t b = bucket_begin; b < bucket_begin + bucket_count && rc == QO_OK; ++b) {
+    uint64_t m = bucket_len(&vs[0].p, b);
+    for (uint32_t k = 0; k < K && rc == QO_OK; ++k) {
+      float norm;
+      rc = decode_bucket(&vs[k], b, &norm, lv, ng);
+      if (rc) break;
+      float scale = norm / (float)vs[k].p.s;
+      for (uint64_t i = 0; i < m; ++i) {
+        float mag = scale * (float)lv[i];
+        dec[(size_t)k * d + i] = (lv[i] != 0 && ng[i]) ? -mag : mag;
+      }
+    }
+    if (rc) break;
+    float *xb = x + (b - bucket_begin) * vs[0].d;
+    for (uint64_t i = 0; i < m; ++i) {
+      float sum = 0.0f;
+      for (uint32_t k = 0; k < K; ++k) sum += dec[(size_t)k * d + i];
+      xb[i] = fmaf(-c, sum, xb[i]);
+    }
+  }
+  free(lv); free(ng); free(dec); free(vs);
+  return rc;
+}
+
 /* ------------------------------------------------------------------------- */
 /* Tensor-aware messages (Sec. 5, "Protocol": matrices with fewer than 10K      */
 /* elements are not quantized; quantization buckets are laid out per matrix).  */

@@ -19,7 +19,12 @@
  *   Code_s/Code'_s pinned: round trip + closed-form lengths (App. A.2 / A.3).
  *   Philox-4x32-10 (the paper names no generator): pinned to the published
  *                 known-answer vectors and an independent big-integer version.
- *   Step          pinned: K=1 d=1 equals plain SGD; linearity vs accumulate.
+ *   Step          pinned: K=1 d=1 equals plain SGD; linearity vs accumulate; the
+ *                 bucket-range form equals the whole step restricted to the range.
+ *   Slices        pinned: buckets i..j of the whole message word for word; beyond
+ *                 2^34 against draws recomputed with the big-integer generator.
+ *   Memory safety: the whole file runs under -fsanitize=address,undefined
+ *                 (sanitize_check.c).
  *   Container (header, offset table, word alignment, bit order) and the
  *   fixed-width field layout: builder-defined, PARITY UNPINNED by the paper
  *   (it gives bit widths only); covered by round trip and size formulas.
@@ -134,6 +139,12 @@ int qo_decode_accumulate(const void *const *msgs, const size_t *bytes, uint32_t 
 /* x_i <- x_i - (eta/K) * sum_{k<K} Decode(M_k)_i   (Algorithm 1, last line). */
 int qo_sgd_step(const void *const *msgs, const size_t *bytes, uint32_t K, float eta,
                 float *x);
+
+/* The step of Algorithm 1 on the coordinates of buckets [bucket_begin, bucket_begin +
+ * bucket_count) only (buckets are independent, Sec. 4); x points at the first coordinate
+ * of bucket `bucket_begin`. */
+int qo_sgd_step_buckets(const void *const *msgs, const size_t *bytes, uint32_t K, float eta,
+                        float *x, uint64_t bucket_begin, uint64_t bucket_count);
 
 /* Word offset (from the payload start) and word count of bucket b's string. */
 int qo_bucket_extent(const void *msg, size_t bytes, uint64_t b, uint64_t *word_off,

@@ -104,6 +104,8 @@ def lib():
         L.qo_decode_accumulate.restype = C.c_int
         L.qo_sgd_step.argtypes = [vp, vp, C.c_uint32, C.c_float, vp]
         L.qo_sgd_step.restype = C.c_int
+        L.qo_sgd_step_buckets.argtypes = [vp, vp, C.c_uint32, C.c_float, vp, C.c_uint64, C.c_uint64]
+        L.qo_sgd_step_buckets.restype = C.c_int
         L.qo_bucket_extent.argtypes = [vp, sz, C.c_uint64, u64p, u64p]
         L.qo_bucket_extent.restype = C.c_int
         L.qo_payload_offset.argtypes = [vp, sz, u64p]
@@ -316,6 +318,21 @@ def sgd_step(msgs, eta: float, x) -> np.ndarray:
     x = _f32(x).copy()
     _chk(lib().qo_sgd_step(ptrs, sizes, len(keep), C.c_float(eta), _ptr(x)), "sgd_step")
     return x
+
+
+def sgd_step_buckets(msgs, eta: float, x, bucket_begin: int, bucket_count: int) -> np.ndarray:
+    """The step on the coordinates of a run of buckets; x holds exactly those coordinates.
+    `msgs` may be a prepared (arrays, pointers, sizes) triple from prepare_messages()."""
+    keep, ptrs, sizes = msgs if isinstance(msgs, tuple) else _msg_arrays(msgs)
+    x = _f32(x).copy()
+    _chk(lib().qo_sgd_step_buckets(ptrs, sizes, len(keep), C.c_float(eta), _ptr(x),
+                                   bucket_begin, bucket_count), "sgd_step_buckets")
+    return x
+
+
+def prepare_messages(msgs):
+    """Pointer and size arrays of a list of messages, for repeated calls on the same list."""
+    return _msg_arrays(msgs)
 
 
 def bucket_extent(msg: np.ndarray, b: int):
