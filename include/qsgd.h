@@ -10,9 +10,10 @@
  *   qsgd_sgd_step           x <- x - (eta/K) sum_l Decode(M_l)   (Alg. 1, last line)
  *
  * Plain C ABI: pointers and sizes only.  Every pointer named *_dev is device
- * memory owned by the caller; everything else is host memory.  The library
- * allocates no device memory; scratch comes in through `workspace_dev`.  All
- * work is queued on the HIP stream passed in (a hipStream_t cast to void*,
+ * memory owned by the caller; everything else is host memory.  The calls on
+ * the hot path allocate no device memory: scratch comes in through
+ * `workspace_dev` (the one exception is qsgd_layout_create, which uploads two
+ * small tables once per layout, outside the path).  All work is queued on the HIP stream passed in (a hipStream_t cast to void*,
  * NULL = the default stream) and the calls return without waiting for it.
  *
  * Return value: 0, or a negative QSGD_ERR_* found on the host before anything
@@ -91,6 +92,15 @@ size_t qsgd_max_encoded_bytes(const qsgd_params *p);
  * device.  Returns 0 for invalid parameters. */
 size_t qsgd_workspace_bytes(const qsgd_params *p, uint32_t K);
 
+/* Bytes of scratch qsgd_encode needs when the message buffer has msg_capacity bytes (a
+ * caller that knows its gradients to be sparse passes a buffer far below the worst case,
+ * and the staging of the bucket strings can shrink with it): at most
+ * qsgd_workspace_bytes(p, 1).  qsgd_encode accepts any workspace from this size up; with
+ * less than the worst case, a part of the vector that codes much longer than its share of
+ * msg_capacity ends the call like a message that does not fit (status QSGD_ERR_CAPACITY
+ * in the header, size needed in its length field).  Host only. */
+size_t qsgd_encode_workspace_bytes(const qsgd_params *p, size_t msg_capacity);
+
 /* Encode (Alg. 1, "M^i <- Encode(g)"; Q_s: Sec. 3.1 Eq. 2 per bucket of Sec. 4;
  * Code_s / Code'_s: Sec. 3.1, App. A.2-A.3).
  *   g_dev          in : n floats, device, 16-byte aligned, finite values
@@ -98,7 +108,8 @@ size_t qsgd_workspace_bytes(const qsgd_params *p, uint32_t K);
  *                  Layout: 64-byte header | table of bucket word offsets
  *                  (Elias codes only) | bucket strings, each word aligned.
  *                  The used length is in the header (qsgd_message_info).
- *   workspace_dev  scratch, device, 16-byte aligned, >= qsgd_workspace_bytes(p, 1);
+ *   workspace_dev  scratch, device, 16-byte aligned, >= qsgd_workspace_bytes(p, 1), or
+ *                  >= qsgd_encode_workspace_bytes(p, msg_capacity) for sparse data;
  *                  contents on entry are ignored, calls sharing it must not overlap
  *   hip_stream     the stream the kernels are queued on
  * Errors: INVALID_ARG, CAPACITY (buffers smaller than the fixed parts), HIP,
@@ -173,17 +184,17 @@ int qsgd_sgd_step_layout(const qsgd_params *p, const qsgd_layout *layout,
 
 /* Encode of a SLICE of a longer vector: as qsgd_encode on the p->n values at g_dev,
  * with the rounding draws of positions index_base .. index_base + p->n - 1 of the
- * whole vector (index_base a multiple of 4; bucket sizes as accepted by the bucket
- * kernels: a multiple of 4, at most 8192, else QSGD_ERR_UNSUPPORTED when index_base
- * is not 0).  If index_base is a multiple of the bucket size, the buckets and levels
- * are exactly those the whole vector would get. */
+ * whole vector (index_base a multiple of 4, else QSGD_ERR_INVALID_ARG; any code and any
+ * bucket size qsgd_encode takes).  If index_base is a multiple of the bucket size, the
+ * buckets and levels are exactly those the whole vector would get. */
 int qsgd_encode_slice(const qsgd_params *p, uint64_t index_base, const float *g_dev,
                       void *msg_dev, size_t msg_capacity, void *workspace_dev,
                       size_t workspace_bytes, void *hip_stream);
 
 /* ---- Double-buffered pass (Sec. 5, "Protocol": quantization and communication are
  * double buffered so that they overlap with computation).  The vector of p->n values is
- * cut into chunks of chunk_elems (a multiple of the bucket size).  For every chunk the K
+ * cut into chunks of chunk_elems (a multiple of the bucket size and of 4; any code and
+ * bucket size the flat calls take).  For every chunk the K
  * peers' slices g_dev[k] + offset are encoded (peer k with stream_id p->stream_id + k)
  * on one internal stream, then decoded, summed and applied to x_dev + offset on a second
  * one, while the next chunk is already being encoded; msg_dev holds 2*K device buffers
@@ -192,8 +203,10 @@ int qsgd_encode_slice(const qsgd_params *p, uint64_t index_base, const float *g_
  * workspace_bytes >= qsgd_workspace_bytes for n = chunk_elems) serve the encode and the
  * decode side.  The work starts after what is queued on hip_stream at the time of the
  * call, and hip_stream continues after the last chunk.  x ends up exactly as after one
- * qsgd_sgd_step over the K whole-vector messages.  Errors as the calls it is made of;
- * after an error the internal streams may still hold work: synchronise the device.
+ * qsgd_sgd_step over the K whole-vector messages.  Errors as the calls it is made of:
+ * sizes and parameters of every chunk are checked before anything is queued, so a
+ * negative return leaves x untouched (only a failing HIP call can end the pass half way;
+ * the internal streams may then still hold work: synchronise the device).
  * qsgd_pipeline_create makes the two streams (default priority) and five events on the
  * current device; calls on one pipeline object must not overlap. */
 typedef struct qsgd_pipeline qsgd_pipeline;
@@ -229,11 +242,18 @@ int qsgd_timing_get(const char *prefix, double *total_ms, uint64_t *launches);
 
 /* Measurement aid, not part of the method: a plain copy kernel (16-byte loads and
  * stores, grid-stride) of `bytes` bytes (a multiple of 16) from src_dev to dst_dev,
- * both device pointers aligned to 16 bytes, on `hip_stream`.  It gives the copy
- * ceiling of the machine the codec is compared with, and a kernel of known HBM
- * traffic that hardware counters can be calibrated against.  Timed as "copy_probe".
+ * both device pointers aligned to 16 bytes, on `hip_stream` (streaming accesses, one
+ * contiguous 16 KiB piece per workgroup).  It gives the copy ceiling of the machine the
+ * codec is compared with, and a kernel of known HBM traffic that hardware counters can
+ * be calibrated against.  Timed as "copy_probe".
  * Returns 0, QSGD_ERR_INVALID_ARG or QSGD_ERR_HIP. */
 int qsgd_copy_probe(void *dst_dev, const void *src_dev, size_t bytes, void *hip_stream);
+
+/* Measurement aid, not part of the method: the same copy with ONE 4-byte load and one
+ * 4-byte store per lane (bytes a multiple of 4), the request size of the kernels that read
+ * message strings word by word.  A second kernel of known traffic, so that the factors of
+ * the hardware counters are known for both request sizes.  Timed as "copywords_probe". */
+int qsgd_copy_probe_words(void *dst_dev, const void *src_dev, size_t bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

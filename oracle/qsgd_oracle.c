@@ -273,19 +273,25 @@ static void quantize_bucket(const qo_params *p, const float *v, uint64_t m,
   }
 }
 
-int qo_quantize(const qo_params *p, const float *g, const float *u_in,
-                uint32_t *levels, uint8_t *neg, float *norms,
-                float *u_out, float *p_out) {
+int qo_quantize_slice(const qo_params *p, const float *g, uint64_t index_offset,
+                      const float *u_in, uint32_t *levels, uint8_t *neg, float *norms,
+                      float *u_out, float *p_out) {
   int rc = check_params(p);
   if (rc) return rc;
   uint64_t d = qo_bucket_size(p), nb = qo_num_buckets(p);
   for (uint64_t b = 0; b < nb; ++b) {
     uint64_t start = b * d, m = bucket_len(p, b);
-    quantize_bucket(p, g + start, m, start, u_in ? u_in + start : NULL,
+    quantize_bucket(p, g + start, m, index_offset + start, u_in ? u_in + start : NULL,
                     levels + start, neg + start, &norms[b],
                     u_out ? u_out + start : NULL, p_out ? p_out + start : NULL);
   }
   return QO_OK;
+}
+
+int qo_quantize(const qo_params *p, const float *g, const float *u_in,
+                uint32_t *levels, uint8_t *neg, float *norms,
+                float *u_out, float *p_out) {
+  return qo_quantize_slice(p, g, 0, u_in, levels, neg, norms, u_out, p_out);
 }
 
 /* ------------------------------------------------------------------------- */

@@ -97,6 +97,12 @@ int qo_quantize(const qo_params *p, const float *g, const float *u_in,
                 uint32_t *levels, uint8_t *neg, float *norms,
                 float *u_out, float *p_out);
 
+/* Q_s of a slice of a longer vector: element i takes the draw of global index
+ * index_offset + i (as qo_encode_slice does); qo_quantize is the case index_offset = 0. */
+int qo_quantize_slice(const qo_params *p, const float *g, uint64_t index_offset,
+                      const float *u_in, uint32_t *levels, uint8_t *neg, float *norms,
+                      float *u_out, float *p_out);
+
 /* Worst-case message size in bytes for these parameters. */
 size_t qo_max_encoded_bytes(const qo_params *p);
 

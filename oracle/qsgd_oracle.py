@@ -84,6 +84,8 @@ def lib():
         L.qo_fixed_field_bits.restype = C.c_uint32
         L.qo_quantize.argtypes = [PP, vp, vp, vp, vp, vp, vp, vp]
         L.qo_quantize.restype = C.c_int
+        L.qo_quantize_slice.argtypes = [PP, vp, C.c_uint64, vp, vp, vp, vp, vp, vp]
+        L.qo_quantize_slice.restype = C.c_int
         L.qo_max_encoded_bytes.argtypes = [PP]
         L.qo_max_encoded_bytes.restype = sz
         L.qo_encode.argtypes = [PP, vp, vp, sz, C.POINTER(sz)]
@@ -195,8 +197,9 @@ def fixed_field_bits(s: int) -> int:
     return int(lib().qo_fixed_field_bits(s))
 
 
-def quantize(p: Params, g, u=None, want_draws: bool = False):
-    """Q_s per bucket.  Returns dict(levels, neg, norms[, u, p])."""
+def quantize(p: Params, g, u=None, want_draws: bool = False, index_offset: int = 0):
+    """Q_s per bucket.  Returns dict(levels, neg, norms[, u, p]).  index_offset: position
+    of g[0] in a longer vector (it selects the draws)."""
     g = _f32(g)
     assert g.size == p.n
     nb = num_buckets(p)
@@ -207,8 +210,8 @@ def quantize(p: Params, g, u=None, want_draws: bool = False):
     u_out = np.zeros(max(p.n, 1), dtype=np.float32) if want_draws else None
     p_out = np.zeros(max(p.n, 1), dtype=np.float32) if want_draws else None
     cp = p.c()
-    _chk(lib().qo_quantize(C.byref(cp), _ptr(g), _ptr(u_in), _ptr(levels), _ptr(neg),
-                           _ptr(norms), _ptr(u_out), _ptr(p_out)), "quantize")
+    _chk(lib().qo_quantize_slice(C.byref(cp), _ptr(g), index_offset, _ptr(u_in), _ptr(levels),
+                                 _ptr(neg), _ptr(norms), _ptr(u_out), _ptr(p_out)), "quantize")
     out = dict(levels=levels[:p.n], neg=neg[:p.n], norms=norms[:nb])
     if want_draws:
         out["u"] = u_out[:p.n]

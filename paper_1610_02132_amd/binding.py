@@ -22,6 +22,7 @@ EXPORTS = [
     "qsgd_layout_max_encoded_bytes", "qsgd_layout_workspace_bytes", "qsgd_encode_layout",
     "qsgd_decode_accumulate_layout", "qsgd_sgd_step_layout", "qsgd_encode_slice",
     "qsgd_pipeline_create", "qsgd_pipeline_destroy", "qsgd_pipeline_step",
+    "qsgd_copy_probe_words", "qsgd_encode_workspace_bytes",
 ]
 
 
@@ -98,6 +99,10 @@ def _load():
     L.qsgd_timing_get.restype = C.c_int
     L.qsgd_copy_probe.argtypes = [vp, vp, sz, vp]
     L.qsgd_copy_probe.restype = C.c_int
+    L.qsgd_copy_probe_words.argtypes = [vp, vp, sz, vp]
+    L.qsgd_copy_probe_words.restype = C.c_int
+    L.qsgd_encode_workspace_bytes.argtypes = [PP, sz]
+    L.qsgd_encode_workspace_bytes.restype = sz
     u64p = C.POINTER(C.c_uint64)
     L.qsgd_layout_create.argtypes = [u64p, u64p, C.c_uint32, C.c_uint64, C.c_uint64,
                                      C.POINTER(vp)]
@@ -270,6 +275,22 @@ def qsgd_copy_probe(dst, src, stream=None) -> None:
     rc = _load().qsgd_copy_probe(dp, sp, sb, _stream(stream))
     if rc:
         raise QsgdError(rc, "qsgd_copy_probe")
+
+
+def qsgd_copy_probe_words(dst, src, stream=None) -> None:
+    """The same copy with one 4-byte load and store per lane."""
+    dp, db = _dev(dst, "dst")
+    sp, sb = _dev(src, "src")
+    if db != sb:
+        raise ValueError("dst and src differ in size")
+    rc = _load().qsgd_copy_probe_words(dp, sp, sb, _stream(stream))
+    if rc:
+        raise QsgdError(rc, "qsgd_copy_probe_words")
+
+
+def qsgd_encode_workspace_bytes(p: Params, msg_capacity: int) -> int:
+    cp = p.c()
+    return int(_load().qsgd_encode_workspace_bytes(C.byref(cp), msg_capacity))
 
 
 class Layout:

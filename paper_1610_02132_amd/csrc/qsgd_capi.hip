@@ -164,8 +164,9 @@ struct EncodePlan {
   uint64_t ws_bytes;
 };
 
-// `teams_target` <= kMaxTeams.
-void plan_encode(const Geometry& g, uint32_t teams_target, EncodePlan& pl) {
+// `teams_target` <= kMaxTeams.  `ws_avail`: bytes of workspace behind the status block; a
+// workspace below the worst case gives every team an equal, smaller region.
+void plan_encode(const Geometry& g, uint32_t teams_target, uint64_t ws_avail, EncodePlan& pl) {
   team_shape(g.d, pl.tw, pl.cpw);
   const uint32_t nb = (uint32_t)g.nb;
   const uint32_t t = std::max(1u, std::min(nb, teams_target));
@@ -179,6 +180,10 @@ void plan_encode(const Geometry& g, uint32_t teams_target, EncodePlan& pl) {
     pl.dst_words = (uint32_t)((g.max_words(g.d) + 2 + 1) & ~(uint64_t)1);
     const uint64_t sub_bits = (uint64_t)pl.cpw * kChunk * g.per_elem;
     pl.sub_words = (uint32_t)(((sub_bits + 31) / 32 + 2 + 1) & ~(uint64_t)1);
+    if (ws_avail >= kTotalsBytes) {
+      const uint64_t share = ((ws_avail - kTotalsBytes) / 4 / pl.teams) & ~(uint64_t)3;
+      pl.region_words = std::min(pl.region_words, share);
+    }
     pl.ws_bytes = kTotalsBytes + (uint64_t)pl.teams * pl.region_words * 4;
   }
   // Survivor ring of Code_s: the small one where several wavefronts share a bucket and the
@@ -195,20 +200,31 @@ void plan_encode(const Geometry& g, uint32_t teams_target, EncodePlan& pl) {
 }
 
 // ---- optional kernel timing -----------------------------------------------------
+// Event pairs are made when timing is switched on (and kept for reuse), so that a timed
+// loop creates none.
 struct TimedLaunch { std::string name; hipEvent_t start, stop; };
+struct EventPair { hipEvent_t start, stop; };
 std::mutex g_timing_mu;
 bool g_timing_on = false;
 std::vector<TimedLaunch> g_launches;
+std::vector<EventPair> g_spare;
+constexpr size_t kSpareEvents = 1024;
 
 struct ScopedTiming {
   hipStream_t st; bool on; TimedLaunch t;
   ScopedTiming(const char* name, hipStream_t s) : st(s), on(false) {
     std::lock_guard<std::mutex> lk(g_timing_mu);
     if (!g_timing_on) return;
-    if (hipEventCreate(&t.start) != hipSuccess) return;
-    if (hipEventCreate(&t.stop) != hipSuccess) { (void)hipEventDestroy(t.start); return; }
+    if (!g_spare.empty()) {
+      t.start = g_spare.back().start; t.stop = g_spare.back().stop;
+      g_spare.pop_back();
+    } else {
+      if (hipEventCreate(&t.start) != hipSuccess) return;
+      if (hipEventCreate(&t.stop) != hipSuccess) { (void)hipEventDestroy(t.start); return; }
+    }
     t.name = name;
     on = hipEventRecord(t.start, st) == hipSuccess;
+    if (!on) g_spare.push_back({t.start, t.stop});
   }
   ~ScopedTiming() {
     if (!on) return;
@@ -351,11 +367,79 @@ int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* ms
 
 }  // namespace
 
-// Plain copy, for calibration and as the machine's copy ceiling.
-__global__ __launch_bounds__(256) void k_copy_probe(float4* __restrict__ dst,
-                                                    const float4* __restrict__ src,
+namespace qsgd {
+
+int validate_encode(const qsgd_params* p, uint64_t index_base, size_t msg_capacity,
+                    size_t workspace_bytes) {
+  Geometry g;
+  int rc = make_geometry(p, g);
+  if (rc) return rc;
+  if (index_base % 4) return QSGD_ERR_INVALID_ARG;
+  const uint64_t fixed_part = 4 * (H_WORDS + g.table_words);
+  if (msg_capacity < fixed_part) return QSGD_ERR_CAPACITY;
+  const uint64_t cap_words = (msg_capacity - fixed_part) / 4;
+  if (g.n == 0) return QSGD_OK;
+  if (!g.bucket_path()) {
+    GenPlan gp;
+    plan_general(g, gp);
+    if (gp.nseg > 0x7FFFFFFFull) return QSGD_ERR_UNSUPPORTED;
+    if (workspace_bytes < kStatusBytes + kTotalsBytes + gp.enc_bytes) return QSGD_ERR_CAPACITY;
+    if (g.code == QSGD_CODE_FIXED && cap_words < g.max_payload_words()) return QSGD_ERR_CAPACITY;
+    return QSGD_OK;
+  }
+  if (workspace_bytes < kStatusBytes + kTotalsBytes) return QSGD_ERR_CAPACITY;
+  EncodePlan pl;
+  int tw, cpw;
+  team_shape(g.d, tw, cpw);
+  const uint32_t target = std::min<uint32_t>(kMaxTeams, (uint32_t)device_cus() * (QSGD_ENC_TEAMS / tw));
+  plan_encode(g, target, workspace_bytes - kStatusBytes, pl);
+  if (g.code != QSGD_CODE_FIXED && pl.region_words < std::min<uint64_t>(64, g.max_words(g.d)))
+    return QSGD_ERR_CAPACITY;
+  if (g.code == QSGD_CODE_FIXED && cap_words < g.max_payload_words()) return QSGD_ERR_CAPACITY;
+  return QSGD_OK;
+}
+
+int validate_decode(const qsgd_params* p, uint32_t K, size_t workspace_bytes) {
+  Geometry g;
+  int rc = make_geometry(p, g);
+  if (rc) return rc;
+  if (K < 1 || K > QSGD_MAX_PEERS) return QSGD_ERR_INVALID_ARG;
+  if (workspace_bytes < qsgd_workspace_bytes(p, K)) return QSGD_ERR_CAPACITY;
+  return QSGD_OK;
+}
+
+}  // namespace qsgd
+
+// Plain copy, for calibration and as the machine's copy ceiling.  Each workgroup copies
+// one contiguous piece of kCopyPiece bytes, a thread has four 16-byte streaming loads in
+// flight before its four stores (measured against grid-stride and cached variants on
+// 8 GB: 5.6 TB/s read + write against 4.6 - 5.4).
+constexpr uint64_t kCopyPiece = 16384;
+__global__ __launch_bounds__(256) void k_copy_probe(float* __restrict__ dst,
+                                                    const float* __restrict__ src,
                                                     uint64_t quads) {
-  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < quads;
+  const uint64_t q0 = (uint64_t)blockIdx.x * (kCopyPiece / 16);
+  const uint64_t q1 = min(q0 + kCopyPiece / 16, quads);
+  float4 v[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const uint64_t i = q0 + (uint64_t)u * 256 + threadIdx.x;
+    if (i < q1) v[u] = qsgd::load_stream(src + 4 * i);
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const uint64_t i = q0 + (uint64_t)u * 256 + threadIdx.x;
+    if (i < q1) qsgd::store_stream(dst + 4 * i, v[u]);
+  }
+}
+
+// The same data read with one 4-byte load per lane and written with one 4-byte store per
+// lane: a second kernel of known traffic, so that the counters' factors are known for both
+// request sizes the library's kernels use.
+__global__ __launch_bounds__(256) void k_copy_probe_words(uint32_t* __restrict__ dst,
+                                                          const uint32_t* __restrict__ src,
+                                                          uint64_t words) {
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < words;
        i += (uint64_t)gridDim.x * 256)
     dst[i] = src[i];
 }
@@ -398,6 +482,18 @@ size_t qsgd_workspace_bytes(const qsgd_params* p, uint32_t K) {
   return (size_t)((bytes + 255) & ~(uint64_t)255);
 }
 
+size_t qsgd_encode_workspace_bytes(const qsgd_params* p, size_t msg_capacity) {
+  Geometry g;
+  if (make_geometry(p, g)) return 0;
+  const size_t worst = qsgd_workspace_bytes(p, 1);
+  if (!g.bucket_path() || g.code == QSGD_CODE_FIXED) return worst;
+  // every team may fill four times its even share of the message, plus one worst-case string
+  const uint64_t teams = std::min<uint64_t>(g.nb, kMaxTeams);
+  const uint64_t share = (uint64_t)msg_capacity / 4 / teams * 4 + g.max_words(g.d) + 8;
+  const uint64_t bytes = kStatusBytes + kTotalsBytes + teams * share * 4;
+  return (size_t)std::min<uint64_t>(worst, (bytes + 255) & ~(uint64_t)255);
+}
+
 static int encode_impl(const qsgd_params* p, const qsgd_layout* L, uint64_t index_base,
                        const float* g_dev, void* msg_dev, size_t msg_capacity,
                        void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
@@ -406,7 +502,6 @@ static int encode_impl(const qsgd_params* p, const qsgd_layout* L, uint64_t inde
   if (rc) return rc;
   if (L && !g.bucket_path()) return QSGD_ERR_UNSUPPORTED;
   if (index_base % 4) return QSGD_ERR_INVALID_ARG;
-  if (index_base && g.n > 0 && !g.bucket_path()) return QSGD_ERR_UNSUPPORTED;
   const uint64_t raw_words = L ? L->raw : 0;
   if (!msg_dev || !aligned16(msg_dev) || !workspace_dev || !aligned16(workspace_dev))
     return QSGD_ERR_INVALID_ARG;
@@ -435,7 +530,8 @@ static int encode_impl(const qsgd_params* p, const qsgd_layout* L, uint64_t inde
     uint8_t* wsb = static_cast<uint8_t*>(workspace_dev) + kStatusBytes + kTotalsBytes;
     GenArgs a;
     std::memset(&a, 0, sizeof a);
-    a.g = g_dev; a.n = g.n; a.d = g.d; a.nb = g.nb; a.spb = gp.spb; a.nseg = gp.nseg;
+    a.g = g_dev; a.index_base = index_base; a.n = g.n; a.d = g.d; a.nb = g.nb; a.spb = gp.spb;
+    a.nseg = gp.nseg;
     a.s = g.s; a.code = g.code; a.norm_mode = g.norm;
     a.key0 = (uint32_t)p->seed; a.key1 = (uint32_t)(p->seed >> 32);
     a.stream_id = p->stream_id; a.iteration = p->iteration;
@@ -487,8 +583,12 @@ static int encode_impl(const qsgd_params* p, const qsgd_layout* L, uint64_t inde
   int tw, cpw;
   team_shape(g.d, tw, cpw);
   const uint32_t target = std::min<uint32_t>(kMaxTeams, (uint32_t)device_cus() * (QSGD_ENC_TEAMS / tw));
-  plan_encode(g, target, pl);
-  if (workspace_bytes < kStatusBytes + pl.ws_bytes) return QSGD_ERR_CAPACITY;
+  if (workspace_bytes < kStatusBytes + kTotalsBytes) return QSGD_ERR_CAPACITY;
+  plan_encode(g, target, workspace_bytes - kStatusBytes, pl);
+  // Elias codes: a region must at least hold one string of typical size; below the
+  // worst case the device reports a region that ran out like a message that did
+  if (g.code != QSGD_CODE_FIXED && pl.region_words < std::min<uint64_t>(64, g.max_words(g.d)))
+    return QSGD_ERR_CAPACITY;
   // fixed width: the size of the message does not depend on the data
   const uint64_t fixed_words =
       g.code != QSGD_CODE_FIXED ? 0
@@ -749,12 +849,24 @@ int qsgd_workspace_status(const void* workspace_dev, void* hip_stream) {
 int qsgd_timing_enable(int on) {
   std::lock_guard<std::mutex> lk(g_timing_mu);
   g_timing_on = on != 0;
+  while (g_timing_on && g_spare.size() < kSpareEvents) {
+    EventPair e;
+    if (hipEventCreate(&e.start) != hipSuccess) return QSGD_ERR_HIP;
+    if (hipEventCreate(&e.stop) != hipSuccess) { (void)hipEventDestroy(e.start); return QSGD_ERR_HIP; }
+    g_spare.push_back(e);
+  }
   return QSGD_OK;
 }
 
 int qsgd_timing_reset(void) {
   std::lock_guard<std::mutex> lk(g_timing_mu);
-  for (auto& t : g_launches) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+  for (auto& t : g_launches) {
+    if (g_spare.size() < kSpareEvents) {
+      g_spare.push_back({t.start, t.stop});
+    } else {
+      (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop);
+    }
+  }
   g_launches.clear();
   return QSGD_OK;
 }
@@ -763,17 +875,29 @@ int qsgd_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* hip_
   if (!dst_dev || !src_dev || (bytes & 15u) || !aligned16(dst_dev) || !aligned16(src_dev))
     return QSGD_ERR_INVALID_ARG;
   if (bytes == 0) return QSGD_OK;
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-    return QSGD_ERR_HIP;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   const uint64_t quads = bytes / 16;
-  const uint32_t blocks = (uint32_t)std::min<uint64_t>((quads + 255) / 256, (uint64_t)cus * 16);
+  const uint64_t blocks = (bytes + kCopyPiece - 1) / kCopyPiece;
+  if (blocks > 0x7FFFFFFFull) return QSGD_ERR_UNSUPPORTED;
   ScopedTiming tm("copy_probe", st);
-  hipLaunchKernelGGL(k_copy_probe, dim3(blocks), dim3(256), 0, st,
-                     reinterpret_cast<float4*>(dst_dev), reinterpret_cast<const float4*>(src_dev),
+  hipLaunchKernelGGL(k_copy_probe, dim3((uint32_t)blocks), dim3(256), 0, st,
+                     reinterpret_cast<float*>(dst_dev), reinterpret_cast<const float*>(src_dev),
                      quads);
+  return hipGetLastError() == hipSuccess ? QSGD_OK : QSGD_ERR_HIP;
+}
+
+int qsgd_copy_probe_words(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream) {
+  if (!dst_dev || !src_dev || (bytes & 3u) || !aligned16(dst_dev) || !aligned16(src_dev))
+    return QSGD_ERR_INVALID_ARG;
+  if (bytes == 0) return QSGD_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const uint64_t words = bytes / 4;
+  const uint32_t blocks =
+      (uint32_t)std::min<uint64_t>((words + 255) / 256, (uint64_t)device_cus() * 64);
+  ScopedTiming tm("copywords_probe", st);
+  hipLaunchKernelGGL(k_copy_probe_words, dim3(blocks), dim3(256), 0, st,
+                     reinterpret_cast<uint32_t*>(dst_dev),
+                     reinterpret_cast<const uint32_t*>(src_dev), words);
   return hipGetLastError() == hipSuccess ? QSGD_OK : QSGD_ERR_HIP;
 }
 

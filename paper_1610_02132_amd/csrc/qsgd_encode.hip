@@ -296,9 +296,12 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
     __syncthreads();
 
     // ---- append the string to the team's region --------------------------------
+    // (a region smaller than the worst case may run out: the string is then dropped, the
+    // count goes on, and the message ends up with the capacity status and the size needed)
     if (tid == 0) a.table[b] = run;  // relative to the region; rebased later
+    const bool room = (uint64_t)run + words <= a.region_words;
     for (uint32_t j = tid; j < words; j += 64 * TW) {
-      region[run + j] = dst[j];
+      if (room) region[run + j] = dst[j];
       dst[j] = 0;
     }
     run += words;
@@ -538,7 +541,9 @@ __global__ __launch_bounds__(256) void k_encode_compact(CompactArgs a) {
   const uint32_t mine = a.totals[j];
   const uint32_t b_begin = j * a.bper;
   const uint32_t b_end = min(b_begin + a.bper, a.nb);
-  const bool fits = base + mine <= a.cap_words && base + mine <= 0xFFFFFFFFull;
+  // (a team whose region ran out has counted on without storing: nothing to copy)
+  const bool fits = base + mine <= a.cap_words && base + mine <= 0xFFFFFFFFull &&
+                    mine <= a.region_words;
   if (fits) {
     const uint32_t* __restrict__ src = a.staging + (uint64_t)j * a.region_words;
     uint32_t* __restrict__ dstp = a.payload + base;

@@ -209,7 +209,7 @@ __global__ __launch_bounds__(64) void k_gen_encode(GenArgs a) {
     qc.stream_id = a.stream_id; qc.iteration = a.iteration;
     const int nchunks = (int)((r.len + kChunk - 1) / kChunk);
     uint32_t rall[kSegChunks][4];
-    draw_all<kSegChunks, ALIGNED>(r.gidx0, lane, qc, rall);
+    draw_all<kSegChunks, ALIGNED>(a.index_base + r.gidx0, lane, qc, rall);
     if (CODE == QSGD_CODE_SPARSE) {
       encode_sparse_wave<kSegChunks, true>(v, rall, nchunks, r.pos0, lane, qc, ring, sub, wo);
     } else if (CODE == QSGD_CODE_DENSE) {
@@ -676,6 +676,7 @@ __device__ __forceinline__ bool parse_in_turns(const DecodeArgs& a, const String
   const bool sparse = a.code == QSGD_CODE_SPARSE;
   for (uint32_t k = 0; k < a.K; ++k) {
     const StringRef sr = refs[k];
+    int my_bad = 0;
     for (uint64_t r = threadIdx.x; r <= sr.ents; r += blockDim.x) {
       uint64_t bitpos = r ? sr.list[2 * (r - 1)] : 32;
       uint64_t pos = r ? sr.list[2 * (r - 1) + 1] : 0;
@@ -687,10 +688,14 @@ __device__ __forceinline__ bool parse_in_turns(const DecodeArgs& a, const String
       // the stretch ends where the next one starts, at the position the list names
       if (ok && !last_stretch) ok = bitpos == stop && pos == sr.list[2 * r + 1];
       if (ok && last_stretch && !sparse) ok = pos == m && bitpos <= sr.endbit;
-      if (!ok) *bad = 1;
+      if (!ok) my_bad = 1;
     }
-    __syncthreads();   // message k is in before message k + 1 adds to the same coordinates
-    if (*bad) return false;
+    // message k is in before message k + 1 adds to the same coordinates; the barrier also
+    // carries the verdict, so that every thread leaves (or stays) together
+    if (__syncthreads_or(my_bad)) {
+      if (threadIdx.x == 0) *bad = 1;
+      return false;
+    }
   }
   return true;
 }

@@ -178,6 +178,7 @@ constexpr uint32_t kEntryBits = 1024;
 
 struct GenArgs {
   const float* g;
+  uint64_t index_base;  // draw index of g[0] (a slice of a longer vector), multiple of 4
   uint64_t n, d, nb;
   uint64_t spb;        // segments per bucket
   uint64_t nseg;       // nb * spb
@@ -205,6 +206,12 @@ struct GenArgs {
   uint64_t fixed_words_full;
   uint64_t fixed_payload_words;
 };
+
+// Host-side checks of an encode / a decode call that only depend on the parameters and the
+// buffer sizes (what the entry points test before they queue anything): 0 or a QSGD_ERR_*.
+int validate_encode(const qsgd_params* p, uint64_t index_base, size_t msg_capacity,
+                    size_t workspace_bytes);
+int validate_decode(const qsgd_params* p, uint32_t K, size_t workspace_bytes);
 
 hipError_t launch_encode_bucket(const EncodeArgs& a, uint32_t code, int tw, int cpw,
                                 uint32_t teams, size_t lds, hipStream_t st);

@@ -7,9 +7,11 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdint>
 #include <new>
 
 #include "qsgd.h"
+#include "qsgd_kernels.hpp"
 
 struct qsgd_pipeline {
   hipStream_t enc = nullptr, dec = nullptr;
@@ -57,14 +59,32 @@ int qsgd_pipeline_step(qsgd_pipeline* pl, const qsgd_params* p, uint64_t chunk_e
       !enc_workspace_dev || !dec_workspace_dev || enc_workspace_dev == dec_workspace_dev)
     return QSGD_ERR_INVALID_ARG;
   const uint64_t d = p->n == 0 ? p->d : std::min<uint64_t>(p->d, p->n);
-  if (d < 4 || d % 4 || chunk_elems == 0 || chunk_elems % d) return QSGD_ERR_INVALID_ARG;
+  // chunks are whole buckets, and every slice starts on a 16-byte boundary
+  if (d < 1 || chunk_elems == 0 || chunk_elems % d || chunk_elems % 4) return QSGD_ERR_INVALID_ARG;
+  // Every chunk is checked before anything is queued, so that an error leaves x untouched:
+  // the full chunks share one geometry, the last one may be shorter.
+  if (p->n > 0) {
+    const uint64_t nchunks = (p->n + chunk_elems - 1) / chunk_elems;
+    const uint64_t which[2] = {0, nchunks - 1};
+    for (int i = 0; i < (nchunks > 1 ? 2 : 1); ++i) {
+      const uint64_t off = which[i] * chunk_elems;
+      qsgd_params pc = *p;
+      pc.n = std::min<uint64_t>(chunk_elems, p->n - off);
+      int rc = qsgd::validate_encode(&pc, off, msg_capacity, workspace_bytes);
+      if (!rc) rc = qsgd::validate_decode(&pc, K, workspace_bytes);
+      if (rc) return rc;
+    }
+  }
+  auto aligned16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+  if (!aligned16(x_dev) || !aligned16(enc_workspace_dev) || !aligned16(dec_workspace_dev))
+    return QSGD_ERR_INVALID_ARG;
+  for (uint32_t k = 0; k < 2 * K; ++k)
+    if (!msg_dev[k] || !aligned16(msg_dev[k])) return QSGD_ERR_INVALID_ARG;
+  for (uint32_t k = 0; k < K; ++k)
+    if (!g_dev[k] || !aligned16(g_dev[k])) return QSGD_ERR_INVALID_ARG;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return QSGD_ERR_HIP;
   if (dev != pl->device) return QSGD_ERR_INVALID_ARG;
-  for (uint32_t k = 0; k < 2 * K; ++k)
-    if (!msg_dev[k]) return QSGD_ERR_INVALID_ARG;
-  for (uint32_t k = 0; k < K; ++k)
-    if (!g_dev[k]) return QSGD_ERR_INVALID_ARG;
   hipStream_t user = reinterpret_cast<hipStream_t>(hip_stream);
   // both streams start after what the caller has queued so far
   if (hipEventRecord(pl->start, user) != hipSuccess ||

@@ -62,3 +62,17 @@ def test_error_strings():
     assert q.qsgd_version() >= 100
     texts = {q.qsgd_strerror(e) for e in (0, -1, -2, -3, -4, -5)}
     assert len(texts) == 6
+
+
+def test_encode_workspace_sized_from_the_message_capacity():
+    """Host arithmetic only: for the stress shape (n = 1e9, s = 4, d = 8192) a message buffer
+    of 28 MB needs a fraction of the worst-case staging, and never more than it."""
+    import paper_1610_02132_amd as q
+    P = q.Params(n=1_000_000_000, s=4, d=8192)
+    worst = q.qsgd_workspace_bytes(P, 1)
+    assert worst > 1_000_000_000
+    small = q.qsgd_encode_workspace_bytes(P, 28_000_000)
+    assert 0 < small <= worst // 4
+    assert q.qsgd_encode_workspace_bytes(P, q.qsgd_max_encoded_bytes(P)) == worst
+    for P2 in (q.Params(n=13_000_000, s=1, d=13_000_000), q.Params(n=10**6, s=256, d=512, code=q.CODE_FIXED)):
+        assert q.qsgd_encode_workspace_bytes(P2, 1 << 20) == q.qsgd_workspace_bytes(P2, 1)

@@ -288,6 +288,99 @@ def test_corrupt_messages_are_flagged():
         assert step(good) == 0
 
 
+@pytest.mark.parametrize("K", [1, 32])
+def test_corrupt_entry_lists_of_long_buckets_are_flagged(K):
+    """Buckets above 8192 values carry a list of entry points behind their string; the
+    readers (all messages at once for K = 1, message after message for K = 32) must refuse
+    a damaged list, leave x alone and stay inside the buffers."""
+    n, s = 3_000_000, 1
+    rng = np.random.default_rng(4)
+    g_host = (rng.standard_normal(n) * ((rng.random(n) < 0.01) * 50.0 + 0.01)).astype(np.float32)
+    g = torch.from_numpy(g_host).cuda()
+    P = q.Params(n=n, s=s, d=n, code=q.CODE_SPARSE, seed=3)
+    status, words, msg = Device(P).encode(g)
+    assert status == 0
+    nw = words.size
+    ents = int(words[-1])
+    assert ents >= 3
+    ws = torch.zeros(max(q.qsgd_workspace_bytes(P, K), 256) // 4, dtype=torch.int32, device="cuda")
+    x0 = torch.from_numpy(W.parameters(W.scaled(W.C4, n)).numpy())
+    good = msg[:nw].clone()
+
+    def step(m):
+        x = x0.clone().cuda()
+        q.qsgd_sgd_step(P, [good] * (K - 1) + [m], 0.1, x, ws)
+        st = q.qsgd_workspace_status(ws)
+        return st, x.cpu()
+
+    st, x = step(good)
+    assert st == 0 and not torch.equal(x, x0)
+    for name, index, value in [
+            ("one entry too many", nw - 1, ents + 1),
+            ("more entries than words", nw - 1, nw),
+            ("entry past the string", nw - 1 - 2 * ents + 2, 32 * nw),         # bit offset of entry 1
+            ("entry in the middle of a code word", nw - 1 - 2 * ents + 2, int(words[nw - 1 - 2 * ents + 2]) + 1),
+            ("wrong position before an entry", nw - 1 - 2 * ents + 3, int(words[nw - 1 - 2 * ents + 3]) + 1),
+            ("entries out of order", nw - 1 - 2 * ents, int(words[nw - 1 - 2 * ents + 2])),
+    ]:
+        bad = good.clone()
+        bad[index] = value
+        st, x = step(bad)
+        assert st == -3, name
+        assert torch.equal(x, x0), name
+    st, x = step(good)
+    assert st == 0
+
+
+def test_encode_with_a_workspace_below_the_worst_case():
+    """Sparse data: the staging of the bucket strings may be far smaller than the worst
+    case (qsgd_encode_workspace_bytes sizes it from the message capacity).  Same message
+    as with the worst-case workspace; data that code longer than the regions or the
+    message buffer allow end with the capacity status, nothing written past either buffer."""
+    n, s, d = 512 * 40_000 + 100, 4, 512
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(12)
+    g = torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, 1e-3, generator=gen)
+    P = q.Params(n=n, s=s, d=d, code=q.CODE_SPARSE, seed=8)
+    worst = q.qsgd_workspace_bytes(P, 1)
+    status, ref, _ = Device(P).encode(g)
+    assert status == 0
+    cap = (int(ref.nbytes * 1.25) + 4096) & ~255
+    sized = q.qsgd_encode_workspace_bytes(P, cap)
+    assert sized <= worst
+    for small in (sized, worst // 3):
+        ws = torch.full((small // 4 + 64,), -1, dtype=torch.int32, device="cuda")
+        msg = torch.full((cap // 4 + 64,), -1, dtype=torch.int32, device="cuda")
+        q.qsgd_encode(P, g, msg[: cap // 4], ws[: small // 4])
+        status, total = q.qsgd_message_status(msg)
+        assert status == 0 and total == ref.nbytes
+        assert np.array_equal(msg.cpu().numpy().view(np.uint32)[: total // 4], ref)
+        assert bool((msg[cap // 4:] == -1).all()) and bool((ws[small // 4:] == -1).all())
+    # a message buffer that is too small: reported with the size needed, not overrun
+    tight = (ref.nbytes * 6 // 10) & ~255
+    msg.fill_(-1)
+    q.qsgd_encode(P, g, msg[: tight // 4], ws[: small // 4])
+    status, need = q.qsgd_message_status(msg)
+    assert status == -2 and need == ref.nbytes
+    assert bool((msg[tight // 4:] == -1).all()) and bool((ws[small // 4:] == -1).all())
+    # regions below what the strings need (the smallest workspace the call takes): the
+    # regions run out before the message buffer does; same report
+    tiny = 256 + 8192 * 12 + 8192 * 64 * 4
+    assert tiny < sized
+    msg.fill_(-1)
+    ws.fill_(-1)
+    q.qsgd_encode(P, g, msg[: cap // 4], ws[: tiny // 4])
+    status, need = q.qsgd_message_status(msg)
+    assert status == -2 and need == ref.nbytes
+    assert bool((msg[cap // 4:] == -1).all()) and bool((ws[tiny // 4:] == -1).all())
+    # and once more with enough room: the buffers are reusable after an overflow
+    q.qsgd_encode(P, g, msg[: cap // 4], ws[: small // 4])
+    status, total = q.qsgd_message_status(msg)
+    assert status == 0 and np.array_equal(msg.cpu().numpy().view(np.uint32)[: total // 4], ref)
+    with pytest.raises(q.QsgdError):      # regions that could not hold one string
+        q.qsgd_encode(P, g, msg[: cap // 4], ws[: 40_000])
+
+
 def test_argument_checks():
     P = q.Params(n=1024, s=4, d=512)
     g = torch.zeros(1024, device="cuda")

@@ -16,12 +16,15 @@ def gradient(n, seed, scale=1e-2):
 
 
 @pytest.mark.parametrize("code,s,d", [(q.CODE_SPARSE, 4, 512), (q.CODE_DENSE, 7, 256),
-                                      (q.CODE_FIXED, 256, 512), (q.CODE_SPARSE, 4, 8192)])
+                                      (q.CODE_FIXED, 256, 512), (q.CODE_SPARSE, 4, 8192),
+                                      # the general path: long buckets, bucket sizes off 4
+                                      (q.CODE_SPARSE, 2, 20_000), (q.CODE_DENSE, 3, 10_004),
+                                      (q.CODE_SPARSE, 4, 1002), (q.CODE_FIXED, 16, 1002)])
 @pytest.mark.parametrize("high", [False, True])
 def test_slice_encode_matches_oracle_slice(code, s, d, high):
     # high: the third bucket straddles element 2^34, where the second Philox counter word
     # changes in the middle of a wavefront
-    n, off = 5 * d + 40, ((1 << 34) - 2 * d - 256 if high else 12 * d)
+    n, off = 5 * d + 40, (((1 << 34) - 2 * d - 256) // 4 * 4 if high else 12 * d)
     P = q.Params(n=n, s=s, d=d, code=code, seed=9, stream_id=2, iteration=1)
     g = gradient(n, 3)
     cap = q.qsgd_max_encoded_bytes(P)
@@ -46,7 +49,11 @@ def test_slice_encode_matches_oracle_slice(code, s, d, high):
 @pytest.mark.parametrize("code,s,d,chunk_buckets", [(q.CODE_SPARSE, 4, 512, 64),
                                                     (q.CODE_FIXED, 256, 512, 100),
                                                     (q.CODE_SPARSE, 4, 8192, 3),
-                                                    (q.CODE_DENSE, 15, 1024, 7)])
+                                                    (q.CODE_DENSE, 15, 1024, 7),
+                                                    # the general path
+                                                    (q.CODE_SPARSE, 2, 20_000, 2),
+                                                    (q.CODE_SPARSE, 4, 1002, 6),
+                                                    (q.CODE_FIXED, 16, 1002, 10)])
 def test_pipeline_equals_the_flat_step(code, s, d, chunk_buckets):
     K, eta = 4, 0.1
     n = 37 * chunk_buckets * d // 10 + 123      # several chunks, a short last one, a short last bucket
@@ -78,6 +85,44 @@ def test_pipeline_equals_the_flat_step(code, s, d, chunk_buckets):
             f"run {rep}: {np.count_nonzero(got != want)} of {n} values differ"
     with pytest.raises(q.QsgdError):
         q.qsgd_pipeline_step(pipe, P, chunk + 4, grads, eta, x, msgs, ws_e, ws_d)
+    pipe.close()
+
+
+def test_pipeline_error_leaves_x_untouched():
+    """Sizes of every chunk are checked before anything is queued: a workspace or a message
+    buffer that only the LAST (or any later) chunk finds too small must not leave x half
+    updated."""
+    code, s, d, K, eta = q.CODE_FIXED, 256, 512, 2, 0.1
+    chunk = 8 * d
+    n = 5 * chunk + 3 * d + 17
+    P = q.Params(n=n, s=s, d=d, code=code, seed=1)
+    grads = [gradient(n, 70 + k) for k in range(K)]
+    x0 = gradient(n, 99, scale=1.0)
+    Pc = q.Params(n=chunk, s=s, d=d, code=code)
+    cap = q.qsgd_max_encoded_bytes(Pc)
+    wsb = q.qsgd_workspace_bytes(Pc, K)
+    good = [torch.zeros(cap // 4, dtype=torch.int32, device="cuda") for _ in range(2 * K)]
+    ws_e = torch.zeros(wsb // 4, dtype=torch.int32, device="cuda")
+    ws_d = torch.zeros(wsb // 4, dtype=torch.int32, device="cuda")
+    pipe = q.Pipeline()
+    for what in ("message buffers too small", "workspace too small", "odd chunk"):
+        x = x0.clone()
+        msgs, we, wd, ch = good, ws_e, ws_d, chunk
+        if what == "message buffers too small":    # fixed width: the size is known on the host
+            msgs = [m[: cap // 8] for m in good]
+        elif what == "workspace too small":
+            we, wd = ws_e[:16], ws_d[:16]
+        else:
+            ch = chunk + 2 * d + 2                 # not a multiple of the bucket size
+        with pytest.raises(q.QsgdError):
+            q.qsgd_pipeline_step(pipe, P, ch, grads, eta, x, msgs, we, wd)
+        torch.cuda.synchronize()
+        assert torch.equal(x, x0), what
+    # and the same call with good buffers works
+    x = x0.clone()
+    q.qsgd_pipeline_step(pipe, P, chunk, grads, eta, x, good, ws_e, ws_d)
+    torch.cuda.synchronize()
+    assert q.qsgd_workspace_status(ws_d) == 0 and not torch.equal(x, x0)
     pipe.close()
 
 
