@@ -47,6 +47,7 @@ extern "C" {
 #define QSGD_ERR_CORRUPT     (-3) /* message does not parse / header does not match params */
 #define QSGD_ERR_HIP         (-4) /* a HIP runtime call failed                             */
 #define QSGD_ERR_UNSUPPORTED (-5) /* valid request this build has no kernel for            */
+#define QSGD_ERR_SCRATCH     (-6) /* request needs more than the built-in scratch holds    */
 
 #define QSGD_MAX_PEERS 64u        /* largest K                                             */
 #define QSGD_HEADER_BYTES 64u
@@ -118,6 +119,22 @@ size_t qsgd_encode_workspace_bytes(const qsgd_params *p, size_t msg_capacity);
 int qsgd_encode(const qsgd_params *p, const float *g_dev, void *msg_dev,
                 size_t msg_capacity, void *workspace_dev, size_t workspace_bytes,
                 void *hip_stream);
+
+/* qsgd_encode for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The scratch is a 64 MiB array inside the library image
+ * (qsgd_static_scratch_bytes()); each GPU the library runs on holds its copy until the
+ * process ends.  Arguments, message and error behaviour as qsgd_encode, minus the
+ * workspace; additionally QSGD_ERR_SCRATCH when qsgd_workspace_bytes(p, 1) exceeds the
+ * array (nothing is queued then).  The call allocates nothing (no hipMalloc / hipFree, no
+ * allocating library routine; while qsgd_timing_enable is on, timing events are taken
+ * from the pool made when it was switched on).  Every call on a GPU shares that GPU's array: calls that
+ * overlap in time on one GPU (different streams, different threads) race, also with
+ * each other's messages; calls on one stream, or ordered by events, are safe.  Nothing
+ * in the array has to survive between calls and nothing has to be cleared. */
+int qsgd_encode_static(const qsgd_params *p, const float *g_dev, void *msg_dev,
+                       size_t msg_capacity, void *hip_stream);
+size_t qsgd_static_scratch_bytes(void);
 
 /* Decode K messages and add them up (Alg. 1, "g^l <- Decode(M^l)" and the sum of
  * its last line):  acc_i <- acc_i + (((0 + g^0_i) + g^1_i) + ... + g^{K-1}_i),

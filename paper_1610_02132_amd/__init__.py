@@ -13,5 +13,5 @@ from .binding import (  # noqa: F401
     Layout, qsgd_decode_accumulate_layout, qsgd_encode_layout, qsgd_layout_info,
     qsgd_layout_max_encoded_bytes, qsgd_layout_workspace_bytes, qsgd_sgd_step_layout,
     Pipeline, qsgd_encode_slice, qsgd_pipeline_step, qsgd_copy_probe_words,
-    qsgd_encode_workspace_bytes,
+    qsgd_encode_workspace_bytes, qsgd_encode_static, qsgd_static_scratch_bytes,
 )

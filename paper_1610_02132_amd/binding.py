@@ -23,6 +23,7 @@ EXPORTS = [
     "qsgd_decode_accumulate_layout", "qsgd_sgd_step_layout", "qsgd_encode_slice",
     "qsgd_pipeline_create", "qsgd_pipeline_destroy", "qsgd_pipeline_step",
     "qsgd_copy_probe_words", "qsgd_encode_workspace_bytes",
+    "qsgd_encode_static", "qsgd_static_scratch_bytes",
 ]
 
 
@@ -103,6 +104,9 @@ def _load():
     L.qsgd_copy_probe_words.restype = C.c_int
     L.qsgd_encode_workspace_bytes.argtypes = [PP, sz]
     L.qsgd_encode_workspace_bytes.restype = sz
+    L.qsgd_encode_static.argtypes = [PP, vp, vp, sz, vp]
+    L.qsgd_encode_static.restype = C.c_int
+    L.qsgd_static_scratch_bytes.restype = sz
     u64p = C.POINTER(C.c_uint64)
     L.qsgd_layout_create.argtypes = [u64p, u64p, C.c_uint32, C.c_uint64, C.c_uint64,
                                      C.POINTER(vp)]
@@ -286,6 +290,22 @@ def qsgd_copy_probe_words(dst, src, stream=None) -> None:
     rc = _load().qsgd_copy_probe_words(dp, sp, sb, _stream(stream))
     if rc:
         raise QsgdError(rc, "qsgd_copy_probe_words")
+
+
+def qsgd_encode_static(p: Params, g, msg, stream=None) -> None:
+    """qsgd_encode with the library's built-in scratch instead of a workspace."""
+    if g.dtype.itemsize != 4 or not g.dtype.is_floating_point or g.numel() != p.n:
+        raise ValueError("g must hold n float32")
+    gp, _ = _dev(g, "g")
+    mp, mbytes = _dev(msg, "msg")
+    cp = p.c()
+    rc = _load().qsgd_encode_static(C.byref(cp), gp, mp, mbytes, _stream(stream))
+    if rc:
+        raise QsgdError(rc, "qsgd_encode_static")
+
+
+def qsgd_static_scratch_bytes() -> int:
+    return int(_load().qsgd_static_scratch_bytes())
 
 
 def qsgd_encode_workspace_bytes(p: Params, msg_capacity: int) -> int:

@@ -456,6 +456,7 @@ const char* qsgd_strerror(int err) {
     case QSGD_ERR_CORRUPT: return "corrupt or mismatching message";
     case QSGD_ERR_HIP: return "HIP runtime error";
     case QSGD_ERR_UNSUPPORTED: return "unsupported configuration";
+    case QSGD_ERR_SCRATCH: return "request exceeds the library's built-in scratch";
     default: return "unknown error";
   }
 }
@@ -661,6 +662,44 @@ static int encode_impl(const qsgd_params* p, const qsgd_layout* L, uint64_t inde
   }
   return QSGD_OK;
 }
+
+// ---- scratch that is part of the library image, for callers that cannot allocate --------
+// One array per GPU the library runs on, held until the process ends.  Host code never
+// uses the array's name as an address: the device address is looked up once per device
+// (hipGetSymbolAddress, with that device current) and kept.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[64] = {nullptr};
+
+static int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return QSGD_ERR_HIP;
+  if (dev < 0 || dev >= 64) return QSGD_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return QSGD_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return QSGD_OK;
+}
+
+int qsgd_encode_static(const qsgd_params* p, const float* g_dev, void* msg_dev,
+                       size_t msg_capacity, void* hip_stream) {
+  const size_t need = qsgd_workspace_bytes(p, 1);
+  if (need == 0) return QSGD_ERR_INVALID_ARG;
+  if (need > kStaticScratchBytes) return QSGD_ERR_SCRATCH;
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc) return rc;
+  // (the encoder ignores what its workspace holds on entry: every word it reads it has
+  // written in the same call, so the last call's contents need no clearing)
+  return encode_impl(p, nullptr, 0, g_dev, msg_dev, msg_capacity, ws, need, hip_stream);
+}
+
+size_t qsgd_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int qsgd_encode(const qsgd_params* p, const float* g_dev, void* msg_dev, size_t msg_capacity,
                 void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
