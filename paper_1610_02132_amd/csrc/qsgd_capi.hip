@@ -348,16 +348,31 @@ int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* ms
     return QSGD_OK;
   }
   // Elias codes: one lane per string.
+  if (a.kloop && g.s <= 127) {
+    // dense strings whose levels fit a byte: the tile decoder
+    const uint32_t W = QSGD_TILE_WIN;
+    uint32_t gw = 1;  // buckets per wavefront: a power of two, gw * K lanes
+    while (gw * 2 * K <= 64 && gw * 2 <= 16) gw *= 2;
+    while (gw > 1 && (g.nb + gw - 1) / gw < (uint64_t)cus * 8) gw /= 2;
+    a.tile_w = W; a.gw = gw;
+    a.win = (uint32_t)std::min<uint64_t>((g.d + 3) & ~(uint64_t)3, W);
+    a.winp = W;
+    const size_t lds = 64 * (size_t)W + 4 * 64 * ((size_t)kStrWin + 1) + 128;   // tile, string rings, Elias table
+    const uint32_t blocks = (uint32_t)((g.nb + gw - 1) / gw);
+    ScopedTiming tm("decode_elias", st);
+    if (launch_decode_tile(a, blocks, lds, st) != hipSuccess) return QSGD_ERR_HIP;
+    return QSGD_OK;
+  }
   const uint32_t win = (uint32_t)std::min<uint64_t>((g.d + 3) & ~(uint64_t)3, 256);
   const uint32_t winp = (win + kChunk - 1) / kChunk * kChunk;
   uint32_t gw = 1;  // buckets per wavefront: a power of two, gw * K lanes, gw * winp floats
   while (gw * 2 * K <= 64 && gw * 2 <= 16) gw *= 2;
   while (gw > 1 && (g.nb + gw - 1) / gw < (uint64_t)cus * 8) gw /= 2;
   a.win = win; a.winp = winp; a.gw = gw; a.rec = std::min(16u, 64u / gw);
-  // LDS: accumulator, record rings, string word rings, dump words; the message-by-message
+  // LDS: accumulator, record rings, string word rings, Elias table, dump words; the message-by-message
   // apply also keeps 3 x 64 words of ring state (the counting apply does not pay for them)
   a.q16 = (g.code == QSGD_CODE_SPARSE && !a.kloop && g.s <= 4) ? 1u : 0u;
-  const size_t lds = 4 * ((size_t)gw * winp + rec_words(a.q16 != 0) + 64 * (kStrWin + 1) + 64 +
+  const size_t lds = 4 * ((size_t)gw * winp + rec_words(a.q16 != 0) + 64 * (kStrWin + 1) + 32 + 64 +
                           (a.kloop ? 192 : 0));
   const uint32_t blocks = (uint32_t)((g.nb + gw - 1) / gw);
   ScopedTiming tm("decode_elias", st);

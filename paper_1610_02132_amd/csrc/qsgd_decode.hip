@@ -18,6 +18,8 @@
 
 namespace qsgd {
 
+constexpr uint32_t kRingStride = kStrWin + 1;   // words of a lane's string ring: kStrWin and the mirror of slot 0
+
 namespace {
 
 // Recursive Elias code (App. A.2), decoder rule unrolled: N = 1; a 0 bit outputs N,
@@ -58,6 +60,31 @@ __device__ __forceinline__ uint32_t omega_peek(uint32_t w, uint32_t& len) {
   if (!t0) { v = 1u; l = 1u; }
   len = l;
   return v;
+}
+
+// Entry of the Elias table for the 7-bit pattern b7 (first stream bit on top): (after, more)
+// = where the bits of the LAST group after its leading 1 start, and how many they are.  The
+// value of the code word is then 2^more + those bits and its length after + more + 1:
+//   0......  the value 1                         (after 0, more 0)
+//   1x0....  one group: 2 or 3                   (after 1, more 1)
+//   1x1ab0.  two groups, the second of x+3 bits  (after 3, more x+2)
+//   1x1ab1.  a third group of (second group)+1 bits follows: values 16 .. 2^16 - 1
+__device__ __forceinline__ uint8_t omega_table_entry(uint32_t b7) {
+  uint32_t after = 0, more = 0;
+  if (b7 & 64u) {
+    const uint32_t g1 = 2u | ((b7 >> 5) & 1u);
+    after = 1; more = 1;
+    if (b7 & 16u) {
+      const uint32_t n1 = g1 + 1u;                                   // bits of the second group
+      const uint32_t g2 = (b7 >> (5u - n1)) & ((1u << n1) - 1u);
+      after = 3; more = n1 - 1u;
+      if ((b7 >> (4u - n1)) & 1u) {                                   // the third group's leading 1
+        after = 2u + n1 + 1u;
+        more = g2;
+      }
+    }
+  }
+  return (uint8_t)(after | (more << 3));
 }
 
 }  // namespace
@@ -327,13 +354,21 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   }
   if (!open) my_scale = 0.f;
 
-  // The lane's view of its string: the last kStrWin words fetched, as a ring in LDS
-  // (word j of the string sits in slot j % kStrWin).  A string is touched once per
-  // kStrFetch words instead of once per record, and the touches of one wavefront
-  // happen together at the top of a round, so a 128-byte line of a message is
-  // pulled from memory a few times rather than once per code word.
-  uint32_t* const slot = swin + (uint32_t)lane * (kStrWin + 1u);
+  // The lane's view of its string: the last kStrWin words fetched, as a ring in LDS: word j
+  // of the string in slot j % kStrWin of the lane's kStrWin + 1 slots; the last slot mirrors
+  // slot 0, so that two consecutive words are always two consecutive slots (one LDS read
+  // of a pair), and the odd stride keeps the lanes on distinct banks.  A string is touched
+  // once per kStrFetch words instead of once per record, and the touches of one wavefront
+  // happen together at the top of a round, so a 128-byte line of a message is pulled from
+  // memory a few times rather than once per code word.
+  uint32_t* const ring = swin + (uint32_t)lane * kRingStride;
+  uint8_t* const otab = reinterpret_cast<uint8_t*>(swin + 64u * kRingStride);   // Elias table
   uint32_t sfill = 0;   // words [sfill - kStrWin, sfill) of the string are in the ring
+  auto ring_put = [&](uint32_t idx, uint32_t word) {
+    const uint32_t sl = idx & (kStrWin - 1u);
+    ring[sl] = word;
+    if (sl == 0) ring[kStrWin] = word;
+  };
   auto fetch = [&]() {
     uint32_t t[kStrFetch];
 #pragma unroll
@@ -342,78 +377,77 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       t[j] = idx < nwords ? str[idx] : 0u;
     }
 #pragma unroll
-    for (uint32_t j = 0; j < kStrFetch; ++j) slot[(sfill + j) & (kStrWin - 1u)] = t[j];
+    for (uint32_t j = 0; j < kStrFetch; ++j) ring_put(sfill + j, t[j]);
     sfill += kStrFetch;
   };
-  // Word wi of the string (zero past its end), out of the ring.
-  auto ring_word = [&](uint32_t wi) -> uint32_t {
-    while (wi >= sfill) fetch();
-    return slot[wi & (kStrWin - 1u)];
+  // The 32 stream bits from bit `at` on, out of the ring (bit j of the stream is bit
+  // 31 - j % 32 of word j / 32).  The parser keeps a bit position instead of a shift
+  // register: the vector ALU bounds this kernel, and this way it only aligns two words.
+  auto peek = [&](uint32_t at) -> uint32_t {
+    const uint32_t off = at & 31u;
+    const uint32_t* const pw = ring + ((at >> 5) & (kStrWin - 1u));
+    const uint32_t wa = pw[0], wb = pw[1];
+    const uint32_t sh = __builtin_amdgcn_alignbit(wa, wb, 32u - off);   // (off = 0 gives wb)
+    return off ? sh : wa;
   };
-  // The unread bits live in a 64-bit register, next bit on top (bit j of the stream
-  // is bit 31-j%32 of word j/32).  Words [0, nwi) have been shifted in, so it
-  // holds 32*nwi - bitpos >= 32 valid bits; word nwi waits in `nextw`, read from
-  // the ring one refill ahead so that its LDS latency is off the parser's critical path.
-  uint64_t bw = 0;
-  uint32_t nwi = 0, nextw = 0;
-  auto consume = [&](uint32_t len) {   // len <= 32
-    bw <<= len;
-    bitpos += len;
-    const uint32_t valid = 32u * nwi - bitpos;
-    if (valid <= 32u) {
-      bw |= (uint64_t)nextw << (32u - valid);
-      ++nwi;
-      nextw = ring_word(nwi);
-    }
+  // Recursive Elias code (App. A.2) through a table: the entry (after, more) of the next 7
+  // bits says where the last group's bits after its leading 1 start and how many they are;
+  // the value is 2^more + those bits, the code word after + more + 1 bits (with its closing
+  // 0, which `open_end` checks: its top bit is set if the word does not end there).
+  // Values below 2^16 (three groups).
+  auto omega_tab = [&](uint32_t w, uint32_t& len, uint32_t& open_end) -> uint32_t {
+    const uint32_t e = otab[w >> 25];
+    const uint32_t after = e & 7u, more = e >> 3;
+    const uint32_t y = w << after;
+    const uint32_t rest = __builtin_amdgcn_ubfe(y, 32u - more, more);   // (more = 0: 0)
+    open_end = y << more;
+    len = after + more + 1u;
+    return (1u << more) | rest;
+  };
+  // a record reads at most the two words at bitpos / 32 (kNarrow) or one more; past the end
+  // of the string the ring may hold anything (those bits lie behind endbit)
+  auto can_parse = [&]() -> bool {
+    return (bitpos >> 5) + (kNarrow ? 1u : 2u) < sfill || sfill >= nwords;
   };
 
   // Reads the next record into pend_*; clears `have` at the end of the string.
   bool bad = false;
   auto advance = [&]() {
+    uint32_t w = peek(bitpos);
     if (kSparse) {
-      if (bitpos >= endbit) { have = false; return; }
-      uint32_t gl, ll, gap, lev;
-      const uint32_t w = (uint32_t)(bw >> 32);
-      gap = omega_peek<3>(w, gl);
-      if (kNarrow) {
-        const uint32_t x = w << gl;
-        pend_neg = x >> 31;
-        lev = omega_peek<LG>(x << 1, ll);
-        consume(gl + 1u + ll);
-      } else {
-        consume(gl);
-        const uint32_t x = (uint32_t)(bw >> 32);
-        pend_neg = x >> 31;
-        lev = omega_peek<LG>(x << 1, ll);
-        consume(1u + ll);
-      }
+      const bool more = bitpos < endbit;
+      uint32_t gl, ll, e1, e2;
+      const uint32_t gap = omega_tab(w, gl, e1);
+      if (!kNarrow) w = peek(bitpos + gl); else w <<= gl;
+      pend_neg = w >> 31;
+      const uint32_t lev = omega_tab(w << 1, ll, e2);
+      bitpos += gl + 1u + ll;
       pend_pos += gap;
       pend_lev = lev;
       // a record that cannot be: remembered here, reported after the parse pass
-      const bool bad_rec = gap == 0 || lev == 0 || lev > s || pend_pos > m || bitpos > endbit;
-      bad = bad || bad_rec;
-      have = !bad_rec;
+      const bool bad_rec = (int)(e1 | e2) < 0 || lev > s || pend_pos > m || bitpos > endbit;
+      bad = bad || (more && bad_rec);
+      have = more && !bad_rec;
     } else {
-      if (pend_pos >= m) { have = false; return; }
-      uint32_t ll;
-      const uint32_t w = (uint32_t)(bw >> 32);
-      const uint32_t lev1 = omega_peek<LG>(w << 1, ll);
-      consume(1u + ll);
+      const bool more = pend_pos < m;
+      uint32_t ll, e2;
+      const uint32_t lev1 = omega_tab(w << 1, ll, e2);
+      bitpos += 1u + ll;
       pend_neg = w >> 31;
       pend_pos += 1;
       pend_lev = lev1 - 1u;
-      if (lev1 == 0 || lev1 > s + 1u || bitpos > endbit) {
-        flag_corrupt(a.status);
-        have = false;
-      }
+      const bool bad_rec = (int)e2 < 0 || lev1 > s + 1u || bitpos > endbit;
+      bad = bad || (more && bad_rec);
+      have = more && !bad_rec;
     }
   };
+  // the table: entry of the 7-bit pattern b7 (first stream bit on top)
+  for (uint32_t b7 = lane; b7 < 128u; b7 += 64) otab[b7] = omega_table_entry(b7);
   if (open) {
     fetch();
-    bw = ((uint64_t)slot[1] << 32) | slot[2];
-    nwi = 3;
-    nextw = slot[3];
+    fetch();
   }
+  __syncthreads();
   if (open) { have = true; advance(); }
   if (bad) { flag_corrupt(a.status); bad = false; }
 
@@ -425,8 +459,8 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   uint32_t qhead = 0, qcnt = 0;            // this lane's ring of queued records
   uint32_t* const accu = reinterpret_cast<uint32_t*>(acc);
   const uint32_t grow = (g < gw ? g : 0u) * winp;   // this lane's accumulator row
-  const uint32_t dump = gw * winp + kRecWords + 64u * (kStrWin + 1u) + (uint32_t)lane;
-  uint32_t* const counts = accu + gw * winp + kRecWords + 64u * (kStrWin + 1u) + 64u;
+  const uint32_t dump = gw * winp + kRecWords + 64u * kRingStride + 32u + (uint32_t)lane;
+  uint32_t* const counts = accu + gw * winp + kRecWords + 64u * kRingStride + 32u + 64u;
   uint32_t* const heads = counts + 64;
   float* const scales = reinterpret_cast<float*>(counts + 128);
   const uint32_t i = (uint32_t)lane * 4u;
@@ -462,7 +496,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   auto commit_pending = [&]() {
     if (tw_pending && sfill == tw_base) {   // (a fetch on demand may have overtaken them)
 #pragma unroll
-      for (uint32_t j = 0; j < kStrFetch; ++j) slot[(sfill + j) & (kStrWin - 1u)] = tw[j];
+      for (uint32_t j = 0; j < kStrFetch; ++j) ring_put(sfill + j, tw[j]);
       sfill += kStrFetch;
     }
     tw_pending = false;
@@ -470,7 +504,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   // Requests the next piece of the string into registers; commit_pending() moves it
   // into the ring later, so the round in between hides the latency.
   auto request_next = [&]() {
-    tw_pending = have && sfill < nwords && sfill - nwi <= kStrWin - kStrFetch;
+    tw_pending = have && sfill < nwords && sfill - (bitpos >> 5) <= kStrWin - kStrFetch;
     tw_base = sfill;
 #pragma unroll
     for (uint32_t j = 0; j < kStrFetch; ++j) {
@@ -511,12 +545,12 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
         commit_pending();
         if constexpr (KLOOP) {
           // dense strings use up a piece in a round or two: have it now
-          if (have && sfill < nwords && sfill - nwi <= kStrWin - kStrFetch) fetch();
+          if (have && sfill < nwords && sfill - (bitpos >> 5) <= kStrWin - kStrFetch) fetch();
         } else {
           request_next();   // arrives while this round parses and applies
         }
         const uint32_t trips = __popcll(needy) >= 32 ? rec : kParse;   // dense data: no imbalance
-        for (uint32_t np = 0; np < trips && have && qcnt < rec; ++np) {
+        for (uint32_t np = 0; np < trips && have && qcnt < rec && can_parse(); ++np) {
           if (kSparse || pend_lev) {   // (Code_s records always carry a level >= 1)
             queue[qidx((uint32_t)lane, (qhead + qcnt) & (rec - 1))] =
                 (qrec_t)((pend_pos - 1u) | (pend_neg << 13) | ((pend_lev - kLevBias) << 14));
@@ -708,7 +742,7 @@ template <int CODE, int LG, int NQ, bool KLOOP, bool Q16>
 __global__ __launch_bounds__(64) void k_decode_elias(DecodeArgs a) {
   if (*a.status != 0) return;
   extern __shared__ uint32_t smem[];
-  // LDS: [acc: gw*winp floats][record rings][string rings: 64*(kStrWin+1)][dump 64]
+  // LDS: [acc: gw*winp floats][record rings][string rings: 64*kRingStride][Elias table: 32][dump 64]
   //      [counts 64][heads 64][scales 64]
   using qrec_t = std::conditional_t<Q16, uint16_t, uint32_t>;
   const uint32_t gw = a.gw, winp = a.winp;
@@ -718,6 +752,305 @@ __global__ __launch_bounds__(64) void k_decode_elias(DecodeArgs a) {
   const uint32_t b0 = blockIdx.x * gw;
   const uint32_t gcount = min(gw, a.nb - b0);  // buckets this wavefront really has
   decode_elias_body<CODE, LG, NQ, KLOOP, Q16>(a, acc, queue, swin, b0, gcount);
+}
+
+// ---- Elias codes, dense strings: a tile of signed levels, summed in registers -----------
+// Where most coordinates carry a nonzero level (Code'_s, or Code_s with s^2 of the order of
+// d: Lemma 3.1 (iii)), a window of W positions holds about as many records per string as
+// positions, and every position receives up to K terms whose fp32 sum has to be taken in
+// message order.  So the two halves of the work are separated by the data layout instead of
+// by queues and turns:
+//   phase 1  every lane parses its own string (bucket g of message k) up to the end of the
+//            window and writes each record's signed level as ONE byte into its own row of a
+//            tile in LDS (64 rows of W bytes, zero = no record): plain stores, no two lanes
+//            share a byte, nothing to wait for.  String words come through a small per-lane
+//            ring that all lanes top up together every kTileBatch records, a batch ahead.
+//   phase 2  lane l owns positions W/64 * l .. of the window in every bucket: for bucket g it
+//            reads its bytes of the rows (g, 0) .. (g, K-1) in message order, turns each
+//            into scale_k * level (the scale comes from the lane that parsed the string) and
+//            adds them up in registers: the sum ((0 + g^0) + g^1) + ... of Alg. 1's last
+//            line by construction, then the update of x (read at the start of the window).
+// Levels must fit a signed byte (s <= 127).
+#ifndef QSGD_TILE_BATCH
+#define QSGD_TILE_BATCH 8
+#endif
+constexpr uint32_t kTileBatch = QSGD_TILE_BATCH;   // records a lane parses between two top-ups of its ring
+
+// NARROW: a whole record (gap, sign, level) fits the 32 bits of one peek.
+template <int CODE, int LG, int NQ, int W, bool NARROW>
+__global__ __launch_bounds__(64) void k_decode_tile(DecodeArgs a) {
+  if (*a.status != 0) return;
+  extern __shared__ uint32_t smem[];
+  constexpr bool kSparse = CODE == QSGD_CODE_SPARSE;
+  constexpr bool kNarrow = !kSparse || NARROW;
+  constexpr uint32_t VPL = W / 64;          // positions of a window a lane owns (2 or 4)
+  static_assert(VPL == 1 || VPL == 2 || VPL == 4, "window of 64, 128 or 256 positions");
+  int8_t* const tile = reinterpret_cast<int8_t*>(smem);          // [64][W]
+  uint32_t* const swin = smem + 64 * W / 4;                       // [64][kRingStride]
+  uint8_t* const otab = reinterpret_cast<uint8_t*>(swin + 64 * kRingStride);   // [128]
+  const uint32_t K = a.K, gw = a.gw, s = a.s, win = a.win;
+  const int lane = threadIdx.x;
+  const uint32_t b0 = blockIdx.x * gw;
+  const uint32_t gcount = min(gw, a.nb - b0);
+  const uint64_t pay = (uint64_t)H_WORDS + a.table_words;
+
+  // ---- open this lane's string -----------------------------------------------------
+  const uint32_t g = lane / K, k = lane - g * K;
+  const uint32_t b = b0 + g;
+  bool have = false;
+  uint32_t m = 0, endbit = 0, nwords = 0;
+  uint32_t pend_pos = 0, pend_lev = 0, pend_neg = 0;   // pend_pos is 1-based
+  const uint32_t* str = nullptr;
+  bool open = false;
+  float my_scale = 0.f;
+  if (g < gcount) {
+    uint64_t base_unused;
+    bucket_extent(a, b, base_unused, m);
+    const uint32_t* msg = a.msgs[k];
+    const uint32_t o0 = msg[H_WORDS + b], o1 = msg[H_WORDS + b + 1];
+    if (o0 < o1 && pay + o1 <= a.msg_words[k]) {
+      nwords = o1 - o0;
+      str = msg + pay + o0;
+      my_scale = __uint_as_float(str[0]) / (float)s;
+      open = true;
+      if (kSparse) {
+        const uint32_t last = str[nwords - 1];
+        endbit = nwords * 32u - 1u - (uint32_t)(__ffs((int)last) - 1);
+        if (last == 0 || endbit < 32u) open = false;
+      } else {
+        endbit = nwords * 32u;
+      }
+    }
+    if (!open) flag_corrupt(a.status);
+  }
+  if (!open) my_scale = 0.f;
+
+  // The lane's view of its string: the last kStrWin words fetched, as a ring in LDS: word j
+  // of the string in slot j % kStrWin of the lane's kStrWin + 1 slots; the last slot mirrors
+  // slot 0, so that two consecutive words are always two consecutive slots (one LDS read
+  // of a pair), and the odd stride keeps the lanes on distinct banks.
+  uint32_t* const ring = swin + (uint32_t)lane * kRingStride;
+  uint32_t sfill = 0;   // words [sfill - kStrWin, sfill) of the string are in the ring
+  auto ring_put = [&](uint32_t idx, uint32_t word) {
+    const uint32_t sl = idx & (kStrWin - 1u);
+    ring[sl] = word;
+    if (sl == 0) ring[kStrWin] = word;
+  };
+  auto fetch = [&]() {
+    uint32_t t[kStrFetch];
+#pragma unroll
+    for (uint32_t j = 0; j < kStrFetch; ++j) {
+      const uint32_t idx = sfill + j;
+      t[j] = idx < nwords ? str[idx] : 0u;
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < kStrFetch; ++j) ring_put(sfill + j, t[j]);
+    sfill += kStrFetch;
+  };
+  // The 32 stream bits from bit `at` on, out of the ring (bit j of the stream is bit
+  // 31 - j % 32 of word j / 32).  No shift register to maintain: the parser keeps a bit
+  // position, and the vector ALU, which bounds this kernel, only aligns two words.
+  auto peek = [&](uint32_t at) -> uint32_t {
+    const uint32_t off = at & 31u;
+    const uint32_t* const pw = ring + ((at >> 5) & (kStrWin - 1u));
+    const uint32_t wa = pw[0], wb = pw[1];
+    const uint32_t sh = __builtin_amdgcn_alignbit(wa, wb, 32u - off);   // (off = 0 gives wb)
+    return off ? sh : wa;
+  };
+  // Recursive Elias code through the table: entry (after, more) of the next 7 bits says
+  // where the last group's bits after its leading 1 start and how many they are; the value
+  // is 2^more + those bits, the code word after + more + 1 bits (with its closing 0, which
+  // `open_end` checks: its top bit is set if the word does not end there).
+  auto omega_tab = [&](uint32_t w, uint32_t& len, uint32_t& open_end) -> uint32_t {
+    const uint32_t e = otab[w >> 25];
+    const uint32_t after = e & 7u, more = e >> 3;
+    const uint32_t y = w << after;
+    const uint32_t rest = __builtin_amdgcn_ubfe(y, 32u - more, more);   // (more = 0: 0)
+    open_end = y << more;
+    len = after + more + 1u;
+    return (1u << more) | rest;
+  };
+  uint32_t bp = 32;   // next unread bit (after the scale)
+  // a record reads at most the two words at bp / 32 (NARROW) or one more; past the end of
+  // the string the ring may hold anything (those bits lie behind endbit)
+  auto can_parse = [&]() -> bool {
+    return (bp >> 5) + (kNarrow ? 1u : 2u) < sfill || sfill >= nwords;
+  };
+  bool bad = false;
+  auto advance = [&]() {
+    uint32_t w = peek(bp);
+    if (kSparse) {
+      const bool more = bp < endbit;
+      uint32_t gl, ll, e1, e2;
+      const uint32_t gap = omega_tab(w, gl, e1);
+      if (!kNarrow) w = peek(bp + gl); else w <<= gl;
+      pend_neg = w >> 31;
+      const uint32_t lev = omega_tab(w << 1, ll, e2);
+      bp += gl + 1u + ll;
+      pend_pos += gap;
+      pend_lev = lev;
+      // a record that cannot be: remembered here, reported after the batch
+      const bool bad_rec = (int)(e1 | e2) < 0 || lev > s || pend_pos > m || bp > endbit;
+      bad = bad || (more && bad_rec);
+      have = more && !bad_rec;
+    } else {
+      const bool more = pend_pos < m;
+      uint32_t ll, e2;
+      const uint32_t lev1 = omega_tab(w << 1, ll, e2);
+      bp += 1u + ll;
+      pend_neg = w >> 31;
+      pend_pos += 1;
+      pend_lev = lev1 - 1u;
+      const bool bad_rec = (int)e2 < 0 || lev1 > s + 1u || bp > endbit;
+      bad = bad || (more && bad_rec);
+      have = more && !bad_rec;
+    }
+  };
+  for (uint32_t b7 = lane; b7 < 128u; b7 += 64) otab[b7] = omega_table_entry(b7);
+  if (open) {
+    fetch();
+    fetch();
+  }
+  __syncthreads();
+  if (open) {
+    have = true;
+    advance();
+  }
+  if (bad) { flag_corrupt(a.status); bad = false; }
+
+  // The next kStrFetch words of the string are always on their way (in registers) while the
+  // ring still holds unread ones: they are requested at a top-up and enter the ring at a
+  // later one, once the lane has used up enough of the ring, a batch of parsing in between.
+  uint32_t tw[kStrFetch];
+  bool tw_pending = false;
+#pragma unroll
+  for (uint32_t j = 0; j < kStrFetch; ++j) tw[j] = 0u;
+  auto commit_pending = [&]() {
+    if (tw_pending && sfill - (bp >> 5) <= kStrWin - kStrFetch) {
+#pragma unroll
+      for (uint32_t j = 0; j < kStrFetch; ++j) ring_put(sfill + j, tw[j]);
+      sfill += kStrFetch;
+      tw_pending = false;
+    }
+  };
+  auto request_next = [&]() {
+    if (!tw_pending && have && sfill < nwords) {
+      tw_pending = true;
+#pragma unroll
+      for (uint32_t j = 0; j < kStrFetch; ++j) {
+        const uint32_t idx = sfill + j;
+        tw[j] = idx < nwords ? str[idx] : 0u;
+      }
+    }
+  };
+
+  for (uint32_t j = lane; j < 64u * W / 4u; j += 64) smem[j] = 0u;
+  __syncthreads();
+
+  int8_t* const row = tile + (uint32_t)lane * W;
+  const uint32_t i = (uint32_t)lane * VPL;   // first window position this lane owns
+  float xr[NQ][VPL];
+  for (uint32_t ws = 0; ws < a.d; ws += win) {
+    const uint32_t wend = ws + win;  // positions (1-based) up to wend fall in this window
+    // ---- string words for this window's first batch; x of this window ---------------------
+    commit_pending();
+    request_next();
+#pragma unroll
+    for (int qi = 0; qi < NQ; ++qi) {
+#pragma unroll
+      for (uint32_t j = 0; j < VPL; ++j) xr[qi][j] = 0.f;
+      if ((uint32_t)qi < gcount) {
+        uint64_t base;
+        uint32_t mb;
+        bucket_extent(a, b0 + (uint32_t)qi, base, mb);
+        const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
+        const float* xp = a.x + base + ws + i;
+        if (i + VPL - 1 < cntw) {
+          if constexpr (VPL == 4) {
+            const float4 v = load_stream(xp);
+            xr[qi][0] = v.x; xr[qi][1] = v.y; xr[qi][2] = v.z; xr[qi][3] = v.w;
+          } else if constexpr (VPL == 2) {
+            const float2 v = *reinterpret_cast<const float2*>(xp);
+            xr[qi][0] = v.x; xr[qi][1] = v.y;
+          } else {
+            xr[qi][0] = xp[0];
+          }
+        } else {
+#pragma unroll
+          for (uint32_t j = 0; j < VPL; ++j)
+            if (i + j < cntw) xr[qi][j] = xp[j];
+        }
+      }
+    }
+    // ---- phase 1: this lane's records of the window into its row of the tile ---------------
+    for (;;) {
+      for (uint32_t t = 0; t < kTileBatch && have && pend_pos <= wend && can_parse(); ++t) {
+        if (kSparse || pend_lev)
+          row[pend_pos - 1u - ws] = (int8_t)(pend_neg ? -(int)pend_lev : (int)pend_lev);
+        advance();
+      }
+      if (__ballot(have && pend_pos <= wend) == 0) break;
+      commit_pending();
+      request_next();
+    }
+    if (bad) { flag_corrupt(a.status); bad = false; }
+    __syncthreads();
+    // ---- phase 2: sum the K rows of every bucket in message order, update x ---------------
+#pragma unroll
+    for (int qi = 0; qi < NQ; ++qi) {
+      if ((uint32_t)qi < gcount) {
+        float sum[VPL];
+#pragma unroll
+        for (uint32_t j = 0; j < VPL; ++j) sum[j] = 0.f;
+        for (uint32_t kk = 0; kk < K; ++kk) {
+          const uint32_t r = (uint32_t)qi * K + kk;   // the lane that parsed string (qi, kk)
+          const float sc = __uint_as_float(lane_bcast(__float_as_uint(my_scale), (int)r));
+          uint32_t w;
+          if constexpr (VPL == 4) {
+            uint32_t* const p = reinterpret_cast<uint32_t*>(tile + r * W) + lane;
+            w = *p;
+            *p = 0u;
+          } else if constexpr (VPL == 2) {
+            uint16_t* const p = reinterpret_cast<uint16_t*>(tile + r * W) + lane;
+            w = *p;
+            *p = 0;
+          } else {
+            uint8_t* const p = reinterpret_cast<uint8_t*>(tile + r * W) + lane;
+            w = *p;
+            *p = 0;
+          }
+#pragma unroll
+          for (uint32_t j = 0; j < VPL; ++j) {
+            const int lev = (int)(int8_t)(w >> (8u * j));
+            sum[j] += sc * (float)lev;     // sign * (scale * level), Eq. (2)
+          }
+        }
+        uint64_t base;
+        uint32_t mb;
+        bucket_extent(a, b0 + (uint32_t)qi, base, mb);
+        const uint32_t cntw = ws < mb ? min(win, mb - ws) : 0u;
+        float* xp = a.x + base + ws + i;
+        float out[VPL];
+#pragma unroll
+        for (uint32_t j = 0; j < VPL; ++j)
+          out[j] = a.step ? fmaf(-a.c, sum[j], xr[qi][j]) : xr[qi][j] + sum[j];
+        if (i + VPL - 1 < cntw) {
+          if constexpr (VPL == 4) {
+            store_stream(xp, make_float4(out[0], out[1], out[2], out[3]));
+          } else if constexpr (VPL == 2) {
+            *reinterpret_cast<float2*>(xp) = make_float2(out[0], out[1]);
+          } else {
+            xp[0] = out[0];
+          }
+        } else {
+#pragma unroll
+          for (uint32_t j = 0; j < VPL; ++j)
+            if (i + j < cntw) xp[j] = out[j];
+        }
+      }
+    }
+    __syncthreads();
+  }
 }
 
 hipError_t launch_decode_check(const DecodeArgs& a, hipStream_t st) {
@@ -784,6 +1117,58 @@ static hipError_t launch_elias_code(const DecodeArgs& a, int lg, uint32_t blocks
   if (nq <= 4) return launch_elias_nq<CODE, 4>(a, lg, blocks, lds, st);
   if (nq <= 8) return launch_elias_nq<CODE, 8>(a, lg, blocks, lds, st);
   return launch_elias_nq<CODE, 16>(a, lg, blocks, lds, st);
+}
+
+template <int CODE, int NQ, int W>
+static hipError_t launch_tile_lg(const DecodeArgs& a, int lg, uint32_t blocks, size_t lds,
+                                 hipStream_t st) {
+  const dim3 grid(blocks), block(64);
+  // the longest record: Elias(d) for the gap, the sign, Elias(s) for the level
+  auto bits_of = [](uint32_t k) {   // length of Elias(k)
+    uint32_t len = 1;
+    while (k > 1) {
+      uint32_t nb = 0;
+      for (uint32_t t = k; t; t >>= 1) ++nb;
+      len += nb;
+      k = nb - 1;
+    }
+    return len;
+  };
+  const bool narrow = a.code != QSGD_CODE_SPARSE || lg <= 2 ||
+                      bits_of(a.d) + 1u + bits_of(a.s) <= 32u;
+#define QSGD_TILE(LGV)                                                                          \
+  if (narrow) hipLaunchKernelGGL((k_decode_tile<CODE, LGV, NQ, W, true>), grid, block, lds, st, a); \
+  else hipLaunchKernelGGL((k_decode_tile<CODE, LGV, NQ, W, false>), grid, block, lds, st, a)
+  switch (lg) {
+    case 1: QSGD_TILE(1); break;
+    case 2: QSGD_TILE(2); break;
+    default: QSGD_TILE(3); break;
+  }
+#undef QSGD_TILE
+  return hipGetLastError();
+}
+
+template <int CODE, int W>
+static hipError_t launch_tile_nq(const DecodeArgs& a, int lg, uint32_t blocks, size_t lds,
+                                 hipStream_t st) {
+  if (a.gw <= 4) return launch_tile_lg<CODE, 4, W>(a, lg, blocks, lds, st);
+  if (a.gw <= 8) return launch_tile_lg<CODE, 8, W>(a, lg, blocks, lds, st);
+  return launch_tile_lg<CODE, 16, W>(a, lg, blocks, lds, st);
+}
+
+// Dense strings, s <= 127 (a level fits a signed byte): a.tile_w = 128 or 256.
+hipError_t launch_decode_tile(const DecodeArgs& a, uint32_t blocks, size_t lds, hipStream_t st) {
+  const uint32_t top = a.code == QSGD_CODE_SPARSE ? a.s : a.s + 1u;
+  const int lg = top <= 3 ? 1 : top <= 15 ? 2 : 3;
+#define QSGD_TILE_W(CODEV)                                                              \
+  switch (a.tile_w) {                                                                    \
+    case 64: return launch_tile_nq<CODEV, 64>(a, lg, blocks, lds, st);                   \
+    case 128: return launch_tile_nq<CODEV, 128>(a, lg, blocks, lds, st);                 \
+    default: return launch_tile_nq<CODEV, 256>(a, lg, blocks, lds, st);                  \
+  }
+  if (a.code == QSGD_CODE_SPARSE) { QSGD_TILE_W(QSGD_CODE_SPARSE) }
+  QSGD_TILE_W(QSGD_CODE_DENSE)
+#undef QSGD_TILE_W
 }
 
 // Groups in the longest level code word: Elias(s) (sparse) or Elias(s + 1) (dense).

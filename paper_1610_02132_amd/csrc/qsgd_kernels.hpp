@@ -149,6 +149,7 @@ struct DecodeArgs {
   uint32_t kloop;        // 1: records are applied message by message (dense messages)
   uint32_t q16;          // 1: 16-bit records (counting apply, s <= 4)
   uint32_t together;     // 1: long buckets, all messages read at once (few shared coordinates)
+  uint32_t tile_w;       // dense strings with s <= 127: window of the tile decoder (128 or 256), else 0
   // fixed width
   uint32_t fixed_bits;
   uint32_t fixed_words_full;
@@ -225,6 +226,10 @@ hipError_t launch_write_empty(uint32_t* header, uint32_t* table, uint32_t code, 
 hipError_t launch_decode_check(const DecodeArgs& a, hipStream_t st);
 hipError_t launch_decode_fixed(const DecodeArgs& a, uint32_t blocks, hipStream_t st);
 hipError_t launch_decode_elias(const DecodeArgs& a, uint32_t blocks, size_t lds, hipStream_t st);
+hipError_t launch_decode_tile(const DecodeArgs& a, uint32_t blocks, size_t lds, hipStream_t st);
+#ifndef QSGD_TILE_WIN
+#define QSGD_TILE_WIN 128
+#endif
 
 hipError_t launch_write_layout_header(uint32_t* header, uint32_t* table, uint32_t code,
                                       uint32_t norm, uint32_t s, uint64_t d, uint64_t n,

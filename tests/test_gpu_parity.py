@@ -109,6 +109,30 @@ def test_sparse_messages_counting_apply(K, d, s):
         run_case(w, norm=q.NORM_MAX)
 
 
+@pytest.mark.parametrize("scale", [1e-3, 3e-39])
+@pytest.mark.parametrize("d,s", [(2048, 2), (8192, 4), (512, 16)])
+def test_cancelling_and_tiny_terms(d, s, scale):
+    """Peers that carry g and -g (terms of one position cancel, sums pass through zero), and
+    magnitudes so small that scales and terms are subnormal: x must still be the oracle's,
+    bit for bit (the accumulating adds neither reorder three terms nor flush small ones)."""
+    n, K = d * 7 + d // 2 + 4, 6
+    gen = torch.Generator().manual_seed(5)
+    base = torch.distributions.StudentT(3.0).sample((n,)).float() * scale
+    base[torch.rand(n, generator=gen) < 0.01] *= 30.0
+    msgs_dev, msgs_host = [], []
+    for k in range(K):
+        g = (base if k % 2 == 0 else -base).clone()
+        P = q.Params(n=n, s=s, d=d, code=q.CODE_SPARSE, seed=3, stream_id=k // 2, iteration=k % 2 * 0)
+        status, words, msg = Device(P).encode(g.cuda())
+        assert status == 0
+        assert compare_encode(P, g.numpy(), words) == 0
+        msgs_dev.append(msg)
+        msgs_host.append(words)
+    P0 = q.Params(n=n, s=s, d=d, code=q.CODE_SPARSE, seed=3)
+    for x in (np.zeros(n, dtype=np.float32), np.linspace(-1, 1, n, dtype=np.float32) * np.float32(scale)):
+        assert check_step(P0, msgs_dev, msgs_host, 0.1, x, K) == 0
+
+
 @pytest.mark.parametrize("s,d", [(10, 8192), (4, 8192), (7, 4096), (2, 2048)])
 def test_dense_chunks_inside_sparse_buckets(s, d):
     """Parameters that promise few nonzero levels (8 s (s + sqrt(d)) <= d) with data that
