@@ -465,7 +465,26 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   float* const scales = reinterpret_cast<float*>(counts + 128);
   const uint32_t i = (uint32_t)lane * 4u;
   // x of one window into registers: quad qi is bucket qi of this wavefront.
+  // The common case, decided per window on the scalar unit: the wavefront has all its NQ
+  // buckets and the window lies inside every one of them.  Then loads and stores need no
+  // per-lane bounds (the general code below costs about a hundred vector instructions per
+  // window, and the vector ALU is what bounds this kernel).
+  uint64_t xbase[NQ];
+  uint32_t xlen_min = 0xFFFFFFFFu;
+#pragma unroll
+  for (int qi = 0; qi < NQ; ++qi) {
+    xbase[qi] = 0;
+    uint32_t mb = 0;
+    if ((uint32_t)qi < gcount) bucket_extent(a, b0 + (uint32_t)qi, xbase[qi], mb);
+    xlen_min = min(xlen_min, mb);
+  }
+  auto whole_window = [&](uint32_t ws) -> bool { return ws + win <= xlen_min && win == kChunk; };
   auto load_x = [&](float4 (&dst)[NQ], uint32_t ws) {
+    if (whole_window(ws)) {
+#pragma unroll
+      for (int qi = 0; qi < NQ; ++qi) dst[qi] = load_stream(a.x + xbase[qi] + ws + i);
+      return;
+    }
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
       dst[qi] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -702,6 +721,22 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     commit_pending();
     request_next();
     // ---- combine the accumulator with x and store ------------------------------------
+    if (whole_window(ws)) {
+#pragma unroll
+      for (int qi = 0; qi < NQ; ++qi) {
+        float* ap = acc + qi * winp + i;
+        const float4 av = *reinterpret_cast<float4*>(ap);
+        *reinterpret_cast<float4*>(ap) = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 xv = xr[qi];
+        if (a.step) {
+          xv.x = fmaf(-a.c, av.x, xv.x); xv.y = fmaf(-a.c, av.y, xv.y);
+          xv.z = fmaf(-a.c, av.z, xv.z); xv.w = fmaf(-a.c, av.w, xv.w);
+        } else {
+          xv.x += av.x; xv.y += av.y; xv.z += av.z; xv.w += av.w;
+        }
+        store_stream(a.x + xbase[qi] + ws + i, xv);
+      }
+    } else {
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
       if ((uint32_t)qi < gcount) {
@@ -730,6 +765,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
           }
         }
       }
+    }
     }
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi)
