@@ -186,17 +186,19 @@ void plan_encode(const Geometry& g, uint32_t teams_target, uint64_t ws_avail, En
     }
     pl.ws_bytes = kTotalsBytes + (uint64_t)pl.teams * pl.region_words * 4;
   }
-  // Survivor ring of Code_s: the small one where several wavefronts share a bucket and the
-  // expected share of nonzero levels, at most s (s + sqrt(d)) / d (Lemma 3.1 (iii)), is
-  // below 1/8: a chunk of 256 values then hardly ever brings the 66 survivors that make
-  // a wavefront start over, and a compute unit holds one more team.
-  pl.ring = kRing;
+  // Code_s where several wavefronts share a bucket: the survivors of all of a wavefront's
+  // chunks are listed before they are coded when the list is expected to be at most half
+  // full, the share of nonzero levels being at most s (s + sqrt(d)) / d (Lemma 3.1 (iii));
+  // a wavefront whose list overflows after all starts over with the direct coder.
+  pl.ring = 0;
+  const uint32_t list = qsgd::list_records(pl.cpw);
   if (g.code == QSGD_CODE_SPARSE && pl.tw >= 2 &&
-      8.0 * g.s * (g.s + std::sqrt((double)g.d)) <= (double)g.d)
-    pl.ring = kRingSmall;
-  const size_t ring_words = g.code == QSGD_CODE_SPARSE ? qsgd::ring_words(pl.ring) : 0;
+      2.0 * g.s * (g.s + std::sqrt((double)g.d)) * (pl.cpw * kChunk) <= (double)g.d * list)
+    pl.ring = list;
+  const size_t ring_words =
+      g.code == QSGD_CODE_SPARSE ? qsgd::ring_words(pl.ring ? pl.ring : qsgd::kRing) : 0;
   pl.lds = 4 * ((size_t)pl.dst_words + (size_t)pl.tw * (pl.sub_words + ring_words)) + 8 * pl.tw +
-           16 * pl.tw + 16;
+           16 * pl.tw + 16 + (pl.ring ? 4 * qsgd::kOmegaTab : 0);
 }
 
 // ---- optional kernel timing -----------------------------------------------------

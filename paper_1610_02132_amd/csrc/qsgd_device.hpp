@@ -75,16 +75,19 @@ __device__ __forceinline__ void philox4x32_10_uniform(uint32_t c0, uint32_t c1, 
 // t = |v| * fl(s/scale) = a*s;  l = floor(t);  p = t - l;  level = l + [u < p],
 // u = (word >> 8) * 2^-24;  t >= s (a = 1 up to rounding) gives the top level.
 // quantize_unclamped leaves out the clamp: its result exceeds s (by one) only for t >= s.
-__device__ __forceinline__ uint32_t quantize_unclamped(float v, float inv, uint32_t word) {
-  // |v| * inv = |v * inv| (inv >= 0); the absolute value then rides on the operands of
-  // the two instructions that read t instead of costing one of its own
-  const float ts = v * inv;
+// ts: t with the sign of the value (|v| * inv = |v * inv|, inv >= 0); the absolute value
+// rides on the operands of the two instructions that read t instead of costing one of its own.
+__device__ __forceinline__ uint32_t quantize_scaled(float ts, uint32_t word) {
   // t >= 0: the conversion truncates, which is floor(t) (saturating for huge or infinite
   // t), and the fraction instruction returns t - floor(t), exact and below 1
   const uint32_t l = (uint32_t)fabsf(ts);
   const float p = __builtin_amdgcn_fractf(fabsf(ts));
   const float u = (float)(word >> 8) * (1.0f / 16777216.0f);
   return l + ((u < p) ? 1u : 0u);
+}
+
+__device__ __forceinline__ uint32_t quantize_unclamped(float v, float inv, uint32_t word) {
+  return quantize_scaled(v * inv, word);
 }
 
 __device__ __forceinline__ uint32_t quantize_one(float v, float inv, float s_f, uint32_t s,

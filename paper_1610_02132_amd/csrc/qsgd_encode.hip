@@ -41,24 +41,38 @@ __device__ __forceinline__ float4 load_quad(const float* __restrict__ gb, uint32
 }  // namespace
 
 // TW wavefronts per bucket, each holding up to CPW chunks of 256 elements.
-// RING: records in a wavefront's survivor ring (Code_s only; see kRingSmall).
-template <int TW, int CPW, int CODE, uint32_t RING = kRing>
-__global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE == 2 ? 1 : QSGD_ENC_WAVES))) void k_encode_bucket(EncodeArgs a) {
+// LIST (Code_s only): 0 = survivors go through a ring that is coded as it fills
+// (encode_sparse_wave); list_records(CPW) = sparse data, survivors of all chunks are listed first
+// (encode_sparse_list).
+template <int TW, int CPW, int CODE, uint32_t LIST = 0>
+__global__ __launch_bounds__(64 * TW)
+    __attribute__((amdgpu_waves_per_eu(CODE == 2 ? 1 : (LIST ? QSGD_ENC_WAVES_LIST : QSGD_ENC_WAVES))))
+    void k_encode_bucket(EncodeArgs a) {
   extern __shared__ uint32_t smem[];
   // LDS: [dst image of the bucket string][TW sub-streams][TW record rings][scratch]
-  constexpr uint32_t kRingW = (CODE == QSGD_CODE_SPARSE) ? ring_words(RING) : 0u;
+  constexpr uint32_t kRingW = (CODE == QSGD_CODE_SPARSE) ? ring_words(LIST ? LIST : kRing) : 0u;
   uint32_t* const dst = smem;
   uint32_t* const sub_all = smem + a.dst_words;
   uint32_t* const ring_all = sub_all + TW * a.sub_words;
   double* const red = reinterpret_cast<double*>(ring_all + TW * kRingW);
   WaveOut* const winfo = reinterpret_cast<WaveOut*>(red + TW);
+  uint32_t* const otab = reinterpret_cast<uint32_t*>(winfo + TW);  // kOmegaTab words if LIST
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
+  // (the wavefront's number is the same in all its lanes: as a scalar, what depends on it --
+  // chunk bounds, LDS bases, the loop over chunks -- stays off the vector unit)
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   uint32_t* const sub = sub_all + wave * a.sub_words;
   uint32_t* const ring = ring_all + wave * kRingW;
 
   for (uint32_t j = tid; j < a.dst_words + TW * a.sub_words; j += 64 * TW) smem[j] = 0;
+  if (LIST) {
+    for (uint32_t k = tid; k < kOmegaTab; k += 64 * TW) {
+      uint64_t code = 0; uint32_t len = 0;
+      if (k) omega_encode(k, code, len);
+      otab[k] = ((uint32_t)code << 8) | len;
+    }
+  }
 
   if (blockIdx.x == 0 && tid == 0) {  // header; length and status are completed later
     uint32_t* h = a.header;
@@ -81,20 +95,36 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
   const uint32_t s = a.s;
   const float s_f = (float)s;
 
+  // Extent of bucket b, as scalars: the same in every lane, and saying so keeps the bounds
+  // and the addresses on the scalar unit.
+  auto extent = [&](uint32_t b, uint64_t& base, uint32_t& m) {
+    bucket_extent(a, b, base, m);
+    base = ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(base >> 32)) << 32) |
+           __builtin_amdgcn_readfirstlane((uint32_t)base);
+    m = __builtin_amdgcn_readfirstlane(m);
+  };
+  constexpr uint32_t kFull = (uint32_t)(TW * CPW) * kChunk;
+
   for (uint32_t b = b_begin; b < b_end; ++b) {
     uint64_t base;
     uint32_t m;
-    bucket_extent(a, b, base, m);
+    extent(b, base, m);
     const float* __restrict__ gb = a.g + base;
 
     // ---- read the bucket once, accumulate the scale --------------------------
     float4 v[CPW];
     float mx = 0.f;
+    if (m == kFull) {  // a full bucket: no bounds to check
 #pragma unroll
-    for (int c = 0; c < CPW; ++c) {
-      const uint32_t cstart = (uint32_t)(wave * CPW + c) * kChunk;
-      v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (cstart < m) v[c] = load_quad(gb, cstart + lane * 4, m);
+      for (int c = 0; c < CPW; ++c)
+        v[c] = load_stream(gb + (uint32_t)(wave * CPW + c) * kChunk + lane * 4);
+    } else {
+#pragma unroll
+      for (int c = 0; c < CPW; ++c) {
+        const uint32_t cstart = (uint32_t)(wave * CPW + c) * kChunk;
+        v[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (cstart < m) v[c] = load_quad(gb, cstart + lane * 4, m);
+      }
     }
     // the draws need no data: they are computed while the loads are in flight
     const uint32_t wstart = (uint32_t)wave * CPW * kChunk;  // bucket position of this wave
@@ -225,9 +255,14 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
       const uint32_t wlen = wstart < m ? min((uint32_t)CPW * kChunk, m - wstart) : 0u;
       const int nchunks = (int)((wlen + kChunk - 1) / kChunk);
       if (CODE == QSGD_CODE_SPARSE) {
-        const bool gave_up =
-            encode_sparse_wave<CPW, false, RING>(v, rall, nchunks, wstart, lane, qc, ring, sub, wo);
-        if (RING < kRing && gave_up) {
+        bool gave_up = false;
+        if constexpr (LIST != 0) {
+          gave_up = encode_sparse_list<CPW, LIST>(v, rall, nchunks, wstart, lane, qc, ring, otab,
+                                                  sub, wo);
+        } else {
+          (void)encode_sparse_wave<CPW, false>(v, rall, nchunks, wstart, lane, qc, ring, sub, wo);
+        }
+        if (LIST && gave_up) {
           // dense data after all: clear what the sub-stream holds and code the wavefront's
           // values chunk by chunk straight from memory
           const uint32_t dirty = min(a.sub_words, ((wo.bits + 31u) >> 5) + 2u);
@@ -258,7 +293,10 @@ __global__ __launch_bounds__(64 * TW) __attribute__((amdgpu_waves_per_eu(CODE ==
       uint32_t prev_last = 0;
 #pragma unroll
       for (int w = 0; w < TW; ++w) {
-        const WaveOut wi = winfo[w];
+        WaveOut wi;
+        wi.first_pos = __builtin_amdgcn_readfirstlane(winfo[w].first_pos);
+        wi.last_pos = __builtin_amdgcn_readfirstlane(winfo[w].last_pos);
+        wi.bits = __builtin_amdgcn_readfirstlane(winfo[w].bits);
         uint32_t glen = 0, gap = 0;
         if (CODE == QSGD_CODE_SPARSE && wi.first_pos) {
           gap = wi.first_pos - prev_last;
@@ -585,8 +623,8 @@ static hipError_t launch_tw_cpw(const EncodeArgs& a, uint32_t code, dim3 grid, s
                                 hipStream_t st) {
   switch (code) {
     case QSGD_CODE_SPARSE:
-      if (TW >= 2 && a.ring == kRingSmall)
-        hipLaunchKernelGGL((k_encode_bucket<TW, CPW, QSGD_CODE_SPARSE, TW >= 2 ? kRingSmall : kRing>),
+      if (TW >= 2 && a.ring == list_records(CPW))
+        hipLaunchKernelGGL((k_encode_bucket<TW, CPW, QSGD_CODE_SPARSE, TW >= 2 ? list_records(CPW) : 0u>),
                            grid, dim3(64 * TW), lds, st, a);
       else
         hipLaunchKernelGGL((k_encode_bucket<TW, CPW, QSGD_CODE_SPARSE>), grid, dim3(64 * TW), lds,

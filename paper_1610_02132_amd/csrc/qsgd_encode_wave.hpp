@@ -18,12 +18,13 @@
 
 namespace qsgd {
 
-// Records in a wavefront's ring (a power of two).  256 holds the survivors of a whole chunk
-// whatever the data.  128 is for teams of several wavefronts on sparse data, where LDS
-// decides how many teams a compute unit holds: a chunk that might not fit (more than
-// 128 - 63 survivors) then makes the wavefront start over with encode_sparse_direct.
+// Records in a wavefront's ring (a power of two): 256 holds the survivors of a whole chunk
+// whatever the data.  On sparse data (see encode_sparse_list) the same words are a plain
+// list of list_records(CPW) records that takes the survivors of all of a wavefront's chunks.
 constexpr uint32_t kRing = 256;
-constexpr uint32_t kRingSmall = 128;
+__host__ __device__ constexpr uint32_t list_records(int cpw) { return cpw >= 8 ? 256u : 128u; }
+// Elias code words of 1 .. kOmegaTab - 1 as (code << 8) | length, entry 0 = 0 (at most 14 bits).
+constexpr uint32_t kOmegaTab = 256;
 __host__ __device__ constexpr uint32_t ring_words(uint32_t ring) { return 3u * ring; }
 constexpr uint32_t kRingWords = ring_words(kRing);
 
@@ -211,6 +212,124 @@ __device__ __forceinline__ bool encode_sparse_wave(const float4 (&v)[CPW],
     head += take;
     count -= take;
   }
+  return false;
+}
+
+// Code_s sub-stream of the wavefront's values on sparse data: stage 1 runs over all
+// chunks first and lists the survivors (position, t with its sign, draw word) in LDS, then
+// one loop codes the list 64 records at a time.  Compared with encode_sparse_wave there is
+// one copy of stage 2 in the kernel instead of one per chunk, no wrap-around in the
+// indices, and the Elias code words of gaps and levels below kOmegaTab come from a table
+// in LDS (`otab`), which keeps a record's whole code inside 32 bits.
+//   list   3 * LIST words of LDS private to this wavefront
+// Returns true when the list would overflow: nothing has been written to `sub` or `out`
+// then, and the caller starts over with encode_sparse_direct.
+template <int CPW, uint32_t LIST>
+__device__ __forceinline__ bool encode_sparse_list(const float4 (&v)[CPW],
+                                                   const uint32_t (&rall)[CPW][4], int nchunks,
+                                                   uint32_t pos0, int lane, const QuantCtx& q,
+                                                   uint32_t* list, const uint32_t* otab,
+                                                   uint32_t* sub, WaveOut& out) {
+  uint32_t count = 0;
+  const uint32_t p1 = pos0 + (uint32_t)lane * 4u + 1u;
+#pragma unroll
+  for (int c = 0; c < CPW; ++c) {
+    if (c >= nchunks) break;
+    const uint32_t (&r)[4] = rall[c];
+    const float ts[4] = {v[c].x * q.inv, v[c].y * q.inv, v[c].z * q.inv, v[c].w * q.inv};
+    bool nz[4];
+    uint64_t mk[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float u = (float)(r[j] >> 8) * (1.0f / 16777216.0f);
+      nz[j] = u < fabsf(ts[j]);
+      mk[j] = __ballot(nz[j]);
+    }
+    const uint32_t cnt = (uint32_t)(__popcll(mk[0]) + __popcll(mk[1]) + __popcll(mk[2]) +
+                                    __popcll(mk[3]));
+    if (cnt == 0) continue;
+    if (count + cnt > LIST) return true;
+    const uint64_t m01 = mk[0] | mk[1], m23 = mk[2] | mk[3];
+    if (((mk[0] & mk[1]) | (mk[2] & mk[3]) | (m01 & m23)) == 0) {
+      // the usual case on sparse data, no lane with two survivors: the lanes below count
+      // once each, and one slot serves whichever of the lane's values survived
+      uint32_t* const at = list + count + bits_below(m01 | m23);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (nz[j]) {
+          at[0] = p1 + (uint32_t)(c * kChunk + j);
+          at[LIST] = __float_as_uint(ts[j]);
+          at[2 * LIST] = r[j];
+        }
+      }
+    } else {
+      uint32_t* at = list + count + bits_below(mk[0]) + bits_below(mk[1]) + bits_below(mk[2]) +
+                     bits_below(mk[3]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (nz[j]) {
+          at[0] = p1 + (uint32_t)(c * kChunk + j);
+          at[LIST] = __float_as_uint(ts[j]);
+          at[2 * LIST] = r[j];
+          ++at;
+        }
+      }
+    }
+    count += cnt;
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (count == 0) return false;
+  uint32_t bits = 0;
+  for (uint32_t head = 0; head < count; head += kWave) {
+    const uint32_t i = head + (uint32_t)lane;
+    const bool live = i < count;
+    uint32_t z = 0, gap = 0, tsb = 0;
+    if (live) {
+      const uint32_t pos = list[i];
+      tsb = list[LIST + i];
+      const uint32_t word = list[2 * LIST + i];
+      const uint32_t prev = i ? list[i - 1u] : 0u;
+      z = min(quantize_scaled(__uint_as_float(tsb), word), q.s);
+      gap = prev ? pos - prev : 0u;
+    }
+    uint32_t len;
+    if (__ballot(max(z, gap) >= kOmegaTab) == 0) {
+      // every code word of the batch from the table: a record is at most 14 + 1 + 14 bits
+      const uint32_t ez = otab[z], eg = otab[gap];
+      const uint32_t ll = ez & 0xFFu, gl = eg & 0xFFu;
+      const uint32_t cl = live ? ll + 1u : 0u;
+      const uint32_t cw = ((tsb >> 31) << ll) | (ez >> 8);
+      const uint32_t code = ((eg >> 8) << cl) | cw;
+      len = gl + cl;
+      const uint32_t incl = wave_incl_scan_u32(len, lane);
+      const uint32_t off = bits + incl - len;
+      if (live) {
+        const uint32_t top = code << (32u - len);
+        const uint32_t w = off >> 5, sh = off & 31u;
+        atomicOr(&sub[w], top >> sh);
+        if (sh + len > 32u) atomicOr(&sub[w + 1], top << (32u - sh));
+      }
+      bits += lane_bcast(incl, 63);
+    } else {
+      uint64_t gc = 0, cw = 0;
+      uint32_t gl = 0, cl = 0;
+      if (live) {
+        uint64_t lc; uint32_t ll;
+        omega_encode(z, lc, ll);
+        cw = ((uint64_t)(tsb >> 31) << ll) | lc;
+        cl = ll + 1u;
+        if (gap) omega_encode(gap, gc, gl);
+      }
+      len = gl + cl;
+      const uint32_t incl = wave_incl_scan_u32(len, lane);
+      const uint32_t off = bits + incl - len;
+      if (live) lds_emit(sub, off, (gc << cl) | cw, len);
+      bits += lane_bcast(incl, 63);
+    }
+  }
+  out.bits = bits;
+  out.first_pos = __builtin_amdgcn_readfirstlane(list[0]);
+  out.last_pos = __builtin_amdgcn_readfirstlane(list[count - 1u]);
   return false;
 }
 

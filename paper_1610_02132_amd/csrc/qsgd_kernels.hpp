@@ -11,12 +11,16 @@ namespace qsgd {
 constexpr uint32_t kMaxBucketFast = 8192;  // largest bucket the register path holds
 constexpr uint32_t kMaxTeams = 8192;       // most teams (regions) one encode uses
 // Team encoder of the Elias codes: waves per SIMD the compiler budgets registers for, and
-// wavefronts of persistent teams per compute unit.  Measured on c5: 4 / 32 -> 0.63 ms per
-// 5e8 values, 4 / 96 -> 0.61, 6 / 96 -> 0.54 (a few spilled registers cost less than the
-// extra wavefronts bring); with the small survivor ring (six teams per compute unit), per
-// 1e9 values: 6 / 72 -> 1.02 ms, 6 / 96 -> 1.00, 6 / 128 -> 0.97, 7 / 120 -> 0.98.
+// wavefronts of persistent teams per compute unit.  Measured on c5 with the survivor ring:
+// 4 / 32 -> 0.63 ms per 5e8 values, 4 / 96 -> 0.61, 6 / 96 -> 0.54.  With the survivor
+// list (sparse data, teams of four wavefronts) LDS lets a compute unit hold five teams, so
+// its kernels are budgeted for five waves and keep every value in a register; per 1e9
+// values: 4 waves 1.09 ms, 5 waves 1.00, 6 waves (registers spilled) 1.00.
 #ifndef QSGD_ENC_WAVES
 #define QSGD_ENC_WAVES 6
+#endif
+#ifndef QSGD_ENC_WAVES_LIST
+#define QSGD_ENC_WAVES_LIST 5
 #endif
 #ifndef QSGD_ENC_TEAMS
 #define QSGD_ENC_TEAMS 128u

@@ -133,21 +133,29 @@ def test_cancelling_and_tiny_terms(d, s, scale):
         assert check_step(P0, msgs_dev, msgs_host, 0.1, x, K) == 0
 
 
-@pytest.mark.parametrize("s,d", [(10, 8192), (4, 8192), (7, 4096), (2, 2048)])
+@pytest.mark.parametrize("s,d", [(10, 8192), (4, 8192), (5, 8192), (7, 4096), (2, 2048)])
 def test_dense_chunks_inside_sparse_buckets(s, d):
-    """Parameters that promise few nonzero levels (8 s (s + sqrt(d)) <= d) with data that
-    breaks the promise: all of a bucket's mass in one or two chunks of 256 values, so that
-    a chunk brings up to 256 survivors.  A wavefront of the team encoder whose small
-    survivor ring cannot take such a chunk starts over with the direct coder."""
-    nb = 24
+    """Parameters that promise few nonzero levels (Lemma 3.1 (iii)) with data that breaks the
+    promise: all of a bucket's mass in one to three chunks of 256 values, or spread evenly
+    over the 2048 values of one wavefront (s sqrt(2048) expected survivors there: more than
+    its list of 256 holds for s = 7, about as many for s = 5).  A wavefront of the team
+    encoder whose survivor list overflows starts over with the direct coder."""
+    nb = 25
     n = nb * d + d // 2
     gen = torch.Generator().manual_seed(1234 + s)
     g = torch.zeros(n)
     for b in range(nb + 1):
         m = min(d, n - b * d)
-        kind = b % 4
+        kind = b % 5
         if kind == 3:                                   # an ordinary bucket
             g[b * d:b * d + m] = torch.randn(m, generator=gen) * 1e-3
+            continue
+        if kind == 4:                                   # one wavefront's share, evenly
+            w0 = 2048 * ((b // 5) % max(1, m // 2048))
+            wl = min(2048, m - w0)
+            mag = 0.9 + 0.2 * torch.rand(wl, generator=gen)
+            sign = torch.where(torch.rand(wl, generator=gen) < 0.5, -1.0, 1.0)
+            g[b * d + w0: b * d + w0 + wl] = mag * sign
             continue
         chunks = torch.randperm(m // 256, generator=gen)[: 1 + kind].tolist()
         for c in chunks:                                # full chunks of similar magnitudes
