@@ -43,6 +43,34 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+// N blocks at once (counter words 0 and 1 per block, words 2 and 3 and the key shared): each
+// round's key is stepped once for all of them, and a wavefront has 2 N independent
+// multiplies in flight instead of two.
+template <int N>
+__device__ __forceinline__ void philox4x32_10_xn(const uint32_t (&c0)[N], const uint32_t (&c1)[N],
+                                                 uint32_t c2, uint32_t c3, uint32_t k0,
+                                                 uint32_t k1, uint32_t (*out)[4]) {
+  asm volatile("" : "+s"(k0), "+s"(k1));
+  uint32_t x0[N], x1[N], x2[N], x3[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) { x0[i] = c0[i]; x1[i] = c1[i]; x2[i] = c2; x3[i] = c3; }
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const uint64_t p0 = (uint64_t)0xD2511F53u * x0[i];
+      const uint64_t p1 = (uint64_t)0xCD9E8D57u * x2[i];
+      const uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), x1[i], k0, 0x96);
+      const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), x3[i], k1, 0x96);
+      x1[i] = (uint32_t)p1; x3[i] = (uint32_t)p0; x0[i] = n0; x2[i] = n2;
+    }
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+#pragma unroll
+  for (int i = 0; i < N; ++i) { out[i][0] = x0[i]; out[i][1] = x1[i]; out[i][2] = x2[i]; out[i][3] = x3[i]; }
+}
+
 // The same block when c1, c2 and c3 are equal in all lanes (c0 is not).  Then the second
 // product of round one and the first product of round two depend on wave-uniform values
 // alone; stating that (readfirstlane) moves them to the scalar unit, two of the twenty

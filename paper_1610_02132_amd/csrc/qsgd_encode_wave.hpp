@@ -16,6 +16,10 @@
 
 #include "qsgd_device.hpp"
 
+#ifndef QSGD_PHILOX_TOGETHER
+#define QSGD_PHILOX_TOGETHER 8
+#endif
+
 namespace qsgd {
 
 // Records in a wavefront's ring (a power of two): 256 holds the survivors of a whole chunk
@@ -94,9 +98,25 @@ __device__ __forceinline__ void draw4_uniform_hi(uint64_t gidx, uint32_t hi, con
 template <int CPW, bool ALIGNED>
 __device__ __forceinline__ void draw_all(uint64_t gidx0, int lane, const QuantCtx& q,
                                          uint32_t (&r)[CPW][4]) {
+  // blocks drawn side by side: the largest of 8, 4, 2 that divides CPW
+  constexpr int kWish = QSGD_PHILOX_TOGETHER;
+  constexpr int kTogether = CPW % kWish == 0 ? kWish : (CPW % 4 == 0 && kWish > 4 ? 4 : (CPW % 2 == 0 && kWish > 1 ? 2 : 1));
+  if constexpr (ALIGNED && kTogether > 1) {
 #pragma unroll
-  for (int c = 0; c < CPW; ++c)
-    draw4<ALIGNED>(gidx0 + (uint64_t)c * kChunk + (uint64_t)lane * 4u, q, r[c]);
+    for (int c = 0; c < CPW; c += kTogether) {
+      uint32_t lo[kTogether], hi[kTogether];
+#pragma unroll
+      for (int i = 0; i < kTogether; ++i) {
+        const uint64_t quad = (gidx0 + (uint64_t)(c + i) * kChunk + (uint64_t)lane * 4u) >> 2;
+        lo[i] = (uint32_t)quad; hi[i] = (uint32_t)(quad >> 32);
+      }
+      philox4x32_10_xn<kTogether>(lo, hi, q.stream_id, q.iteration, q.key0, q.key1, &r[c]);
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < CPW; ++c)
+      draw4<ALIGNED>(gidx0 + (uint64_t)c * kChunk + (uint64_t)lane * 4u, q, r[c]);
+  }
 }
 
 // Stage 2 on `take` (1..64) records starting at ring slot `head`.
@@ -230,11 +250,13 @@ __device__ __forceinline__ bool encode_sparse_list(const float4 (&v)[CPW],
                                                    uint32_t pos0, int lane, const QuantCtx& q,
                                                    uint32_t* list, const uint32_t* otab,
                                                    uint32_t* sub, WaveOut& out) {
+  // (chunks past the end of the data hold zeros, which never survive: no test of nchunks;
+  // and a list that would overflow is not written to any more while the count goes on, so
+  // that the loop has one way out)
   uint32_t count = 0;
   const uint32_t p1 = pos0 + (uint32_t)lane * 4u + 1u;
 #pragma unroll
   for (int c = 0; c < CPW; ++c) {
-    if (c >= nchunks) break;
     const uint32_t (&r)[4] = rall[c];
     const float ts[4] = {v[c].x * q.inv, v[c].y * q.inv, v[c].z * q.inv, v[c].w * q.inv};
     bool nz[4];
@@ -247,10 +269,10 @@ __device__ __forceinline__ bool encode_sparse_list(const float4 (&v)[CPW],
     }
     const uint32_t cnt = (uint32_t)(__popcll(mk[0]) + __popcll(mk[1]) + __popcll(mk[2]) +
                                     __popcll(mk[3]));
-    if (cnt == 0) continue;
-    if (count + cnt > LIST) return true;
     const uint64_t m01 = mk[0] | mk[1], m23 = mk[2] | mk[3];
-    if (((mk[0] & mk[1]) | (mk[2] & mk[3]) | (m01 & m23)) == 0) {
+    if (cnt == 0 || count + cnt > LIST) {
+      // nothing to list, or no room
+    } else if (((mk[0] & mk[1]) | (mk[2] & mk[3]) | (m01 & m23)) == 0) {
       // the usual case on sparse data, no lane with two survivors: the lanes below count
       // once each, and one slot serves whichever of the lane's values survived
       uint32_t* const at = list + count + bits_below(m01 | m23);
@@ -279,6 +301,7 @@ __device__ __forceinline__ bool encode_sparse_list(const float4 (&v)[CPW],
   }
   __builtin_amdgcn_wave_barrier();
   if (count == 0) return false;
+  if (count > LIST) return true;
   uint32_t bits = 0;
   for (uint32_t head = 0; head < count; head += kWave) {
     const uint32_t i = head + (uint32_t)lane;
