@@ -280,6 +280,11 @@ def measure(args, wname: str, torch, np, q, W, cpu_seconds: float) -> dict:
     copy_ms, copy_cnt = q.qsgd_timing_get("copy_probe")
     q.qsgd_timing_reset()
     copy_gbps = copy_cnt * 8.0 * n_arena / (copy_ms * 1e-3) / 1e9
+    # the second kernel of known traffic (4-byte requests), so that a hardware-counter run of
+    # this command holds both calibration points; on a slice, it is not a bandwidth figure
+    nw = min(n_arena, 1 << 26)
+    q.qsgd_copy_probe_words(dst[:nw], src[:nw])
+    torch.cuda.synchronize()
     del dst
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload, and the ----

@@ -833,9 +833,14 @@ __global__ __launch_bounds__(64) void k_decode_tile(DecodeArgs a) {
   // ---- open this lane's string -----------------------------------------------------
   const uint32_t g = lane / K, k = lane - g * K;
   const uint32_t b = b0 + g;
-  bool have = false;
+  // The record a lane has read and not yet stored: 1-based position (kDone: none, the
+  // string has ended or is damaged), level and sign.  One number answers both "is there a
+  // record" and "does it fall in this window", which keeps the parse loop's bookkeeping
+  // off the scalar unit: every instruction of that loop, scalar ones included, is a step
+  // of a chain that one lane's string forces to be serial.
+  constexpr uint32_t kDone = 0xFFFFFFFFu;
   uint32_t m = 0, endbit = 0, nwords = 0;
-  uint32_t pend_pos = 0, pend_lev = 0, pend_neg = 0;   // pend_pos is 1-based
+  uint32_t pend_pos = kDone, pend_lev = 0, pend_neg = 0;
   const uint32_t* str = nullptr;
   bool open = false;
   float my_scale = 0.f;
@@ -907,13 +912,15 @@ __global__ __launch_bounds__(64) void k_decode_tile(DecodeArgs a) {
     return (1u << more) | rest;
   };
   uint32_t bp = 32;   // next unread bit (after the scale)
-  // a record reads at most the two words at bp / 32 (NARROW) or one more; past the end of
-  // the string the ring may hold anything (those bits lie behind endbit)
-  auto can_parse = [&]() -> bool {
-    return (bp >> 5) + (kNarrow ? 1u : 2u) < sfill || sfill >= nwords;
+  // A record reads at most the two words at bp / 32 (NARROW) or one more, so the lane may
+  // parse while bp is below `plim` (no limit once the whole string is in the ring: past its
+  // end the ring may hold anything, those bits lie behind endbit).
+  auto parse_limit = [&]() -> uint32_t {
+    return sfill >= nwords ? 0xFFFFFFFFu : (sfill - (kNarrow ? 1u : 2u)) * 32u;
   };
-  bool bad = false;
-  auto advance = [&]() {
+  uint32_t bad = 0;   // a record that cannot be: remembered here, reported after the batch
+  // Reads the next record; `pos` is the position of the one before (0 at the start).
+  auto advance = [&](uint32_t pos) {
     uint32_t w = peek(bp);
     if (kSparse) {
       const bool more = bp < endbit;
@@ -923,23 +930,22 @@ __global__ __launch_bounds__(64) void k_decode_tile(DecodeArgs a) {
       pend_neg = w >> 31;
       const uint32_t lev = omega_tab(w << 1, ll, e2);
       bp += gl + 1u + ll;
-      pend_pos += gap;
+      pos += gap;
       pend_lev = lev;
-      // a record that cannot be: remembered here, reported after the batch
-      const bool bad_rec = (int)(e1 | e2) < 0 || lev > s || pend_pos > m || bp > endbit;
-      bad = bad || (more && bad_rec);
-      have = more && !bad_rec;
+      // (no short cuts between the tests: as plain mask arithmetic they cost no branch)
+      const bool bad_rec = ((int)(e1 | e2) < 0) | (lev > s) | (pos > m) | (bp > endbit);
+      bad |= (more & bad_rec) ? 1u : 0u;
+      pend_pos = (more & !bad_rec) ? pos : kDone;
     } else {
-      const bool more = pend_pos < m;
+      const bool more = pos < m;
       uint32_t ll, e2;
       const uint32_t lev1 = omega_tab(w << 1, ll, e2);
       bp += 1u + ll;
       pend_neg = w >> 31;
-      pend_pos += 1;
       pend_lev = lev1 - 1u;
-      const bool bad_rec = (int)e2 < 0 || lev1 > s + 1u || bp > endbit;
-      bad = bad || (more && bad_rec);
-      have = more && !bad_rec;
+      const bool bad_rec = ((int)e2 < 0) | (lev1 > s + 1u) | (bp > endbit);
+      bad |= (more & bad_rec) ? 1u : 0u;
+      pend_pos = (more & !bad_rec) ? pos + 1u : kDone;
     }
   };
   for (uint32_t b7 = lane; b7 < 128u; b7 += 64) otab[b7] = omega_table_entry(b7);
@@ -948,11 +954,8 @@ __global__ __launch_bounds__(64) void k_decode_tile(DecodeArgs a) {
     fetch();
   }
   __syncthreads();
-  if (open) {
-    have = true;
-    advance();
-  }
-  if (bad) { flag_corrupt(a.status); bad = false; }
+  if (open) advance(0u);
+  if (bad) { flag_corrupt(a.status); bad = 0; }
 
   // The next kStrFetch words of the string are always on their way (in registers) while the
   // ring still holds unread ones: they are requested at a top-up and enter the ring at a
@@ -970,7 +973,7 @@ __global__ __launch_bounds__(64) void k_decode_tile(DecodeArgs a) {
     }
   };
   auto request_next = [&]() {
-    if (!tw_pending && have && sfill < nwords) {
+    if (!tw_pending && pend_pos != kDone && sfill < nwords) {
       tw_pending = true;
 #pragma unroll
       for (uint32_t j = 0; j < kStrFetch; ++j) {
@@ -1020,16 +1023,21 @@ __global__ __launch_bounds__(64) void k_decode_tile(DecodeArgs a) {
     }
     // ---- phase 1: this lane's records of the window into its row of the tile ---------------
     for (;;) {
-      for (uint32_t t = 0; t < kTileBatch && have && pend_pos <= wend && can_parse(); ++t) {
-        if (kSparse || pend_lev)
-          row[pend_pos - 1u - ws] = (int8_t)(pend_neg ? -(int)pend_lev : (int)pend_lev);
-        advance();
+      const uint32_t plim = parse_limit();
+      for (uint32_t t = 0; t < kTileBatch; ++t) {
+        const bool act = pend_pos <= wend && bp < plim;
+        if (__ballot(act) == 0) break;
+        if (act) {
+          if (kSparse || pend_lev)
+            row[pend_pos - 1u - ws] = (int8_t)(pend_neg ? -(int)pend_lev : (int)pend_lev);
+          advance(pend_pos);
+        }
       }
-      if (__ballot(have && pend_pos <= wend) == 0) break;
+      if (__ballot(pend_pos <= wend) == 0) break;
       commit_pending();
       request_next();
     }
-    if (bad) { flag_corrupt(a.status); bad = false; }
+    if (bad) { flag_corrupt(a.status); bad = 0; }
     __syncthreads();
     // ---- phase 2: sum the K rows of every bucket in message order, update x ---------------
 #pragma unroll
