@@ -323,12 +323,17 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   // ---- open this lane's string -----------------------------------------------------
   const uint32_t g = lane / K, k = lane - g * K;
   const uint32_t b = b0 + g;
-  bool have = false;      // a decoded record is waiting in (pend_pos, pend_lev, pend_neg)
+  // The record a lane has decoded and not yet queued: (pend_pos, pend_lev, pend_neg), pend_pos
+  // 1-based, kDone when there is none (the string has ended or is damaged).  One number says
+  // both whether there is a record and where it falls, and the parse loop below has one
+  // predicate per trip: every instruction of that loop, scalar ones included, is a step of
+  // a chain that a lane's string forces to be serial.
+  constexpr uint32_t kDone = 0xFFFFFFFFu;
   uint32_t m = 0;         // elements in this lane's bucket
   uint32_t endbit = 0;    // records end here
   uint32_t bitpos = 32;   // next unread bit (after the scale)
   uint32_t nwords = 0;
-  uint32_t pend_pos = 0, pend_lev = 0, pend_neg = 0;  // pend_pos is 1-based
+  uint32_t pend_pos = kDone, pend_lev = 0, pend_neg = 0;
   const uint32_t* str = nullptr;
   bool open = false;
   float my_scale = 0.f;
@@ -404,15 +409,17 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     len = after + more + 1u;
     return (1u << more) | rest;
   };
-  // a record reads at most the two words at bitpos / 32 (kNarrow) or one more; past the end
-  // of the string the ring may hold anything (those bits lie behind endbit)
-  auto can_parse = [&]() -> bool {
-    return (bitpos >> 5) + (kNarrow ? 1u : 2u) < sfill || sfill >= nwords;
+  // A record reads at most the two words at bitpos / 32 (kNarrow) or one more, so a lane may
+  // parse while bitpos is below this limit (none once the whole string is in the ring: past
+  // its end the ring may hold anything, those bits lie behind endbit).
+  auto parse_limit = [&]() -> uint32_t {
+    return sfill >= nwords ? 0xFFFFFFFFu : (sfill - (kNarrow ? 1u : 2u)) * 32u;
   };
 
-  // Reads the next record into pend_*; clears `have` at the end of the string.
-  bool bad = false;
-  auto advance = [&]() {
+  // Reads the next record into pend_*; `pos` is the position of the one before (0 at the
+  // start of the string).  pend_pos = kDone at the end of the string.
+  uint32_t bad = 0;   // a record that cannot be: remembered here, reported after the parse pass
+  auto advance = [&](uint32_t pos) {
     uint32_t w = peek(bitpos);
     if (kSparse) {
       const bool more = bitpos < endbit;
@@ -422,23 +429,22 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       pend_neg = w >> 31;
       const uint32_t lev = omega_tab(w << 1, ll, e2);
       bitpos += gl + 1u + ll;
-      pend_pos += gap;
+      pos += gap;
       pend_lev = lev;
-      // a record that cannot be: remembered here, reported after the parse pass
-      const bool bad_rec = (int)(e1 | e2) < 0 || lev > s || pend_pos > m || bitpos > endbit;
-      bad = bad || (more && bad_rec);
-      have = more && !bad_rec;
+      // (no short cuts between the tests: as plain mask arithmetic they cost no branch)
+      const bool bad_rec = ((int)(e1 | e2) < 0) | (lev > s) | (pos > m) | (bitpos > endbit);
+      bad |= (more & bad_rec) ? 1u : 0u;
+      pend_pos = (more & !bad_rec) ? pos : kDone;
     } else {
-      const bool more = pend_pos < m;
+      const bool more = pos < m;
       uint32_t ll, e2;
       const uint32_t lev1 = omega_tab(w << 1, ll, e2);
       bitpos += 1u + ll;
       pend_neg = w >> 31;
-      pend_pos += 1;
       pend_lev = lev1 - 1u;
-      const bool bad_rec = (int)e2 < 0 || lev1 > s + 1u || bitpos > endbit;
-      bad = bad || (more && bad_rec);
-      have = more && !bad_rec;
+      const bool bad_rec = ((int)e2 < 0) | (lev1 > s + 1u) | (bitpos > endbit);
+      bad |= (more & bad_rec) ? 1u : 0u;
+      pend_pos = (more & !bad_rec) ? pos + 1u : kDone;
     }
   };
   // the table: entry of the 7-bit pattern b7 (first stream bit on top)
@@ -448,8 +454,8 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     fetch();
   }
   __syncthreads();
-  if (open) { have = true; advance(); }
-  if (bad) { flag_corrupt(a.status); bad = false; }
+  if (open) advance(0u);
+  if (bad) { flag_corrupt(a.status); bad = 0; }
 
   for (uint32_t j = lane; j < gw * winp; j += 64) acc[j] = 0.f;
   __syncthreads();
@@ -523,7 +529,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   // Requests the next piece of the string into registers; commit_pending() moves it
   // into the ring later, so the round in between hides the latency.
   auto request_next = [&]() {
-    tw_pending = have && sfill < nwords && sfill - (bitpos >> 5) <= kStrWin - kStrFetch;
+    tw_pending = pend_pos != kDone && sfill < nwords && sfill - (bitpos >> 5) <= kStrWin - kStrFetch;
     tw_base = sfill;
 #pragma unroll
     for (uint32_t j = 0; j < kStrFetch; ++j) {
@@ -557,33 +563,38 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       // A parse pass costs as many trips of the divergent loop as its busiest lane
       // takes, so passes are short and start when most lanes can use all the trips
       // (their rings have room), or when a lane is out of records for this window.
-      const uint64_t needy = __ballot(have && pend_pos <= wend);
-      const uint32_t nroom = (uint32_t)__popcll(__ballot(have && qcnt + kRoom <= rec));
+      const uint64_t needy = __ballot(pend_pos <= wend);
+      const uint32_t nroom = (uint32_t)__popcll(__ballot(pend_pos != kDone && qcnt + kRoom <= rec));
       if (needy != 0 || nroom >= kParseLanes) {
         // top up the string rings together, then parse
         commit_pending();
         if constexpr (KLOOP) {
           // dense strings use up a piece in a round or two: have it now
-          if (have && sfill < nwords && sfill - (bitpos >> 5) <= kStrWin - kStrFetch) fetch();
+          if (pend_pos != kDone && sfill < nwords && sfill - (bitpos >> 5) <= kStrWin - kStrFetch) fetch();
         } else {
           request_next();   // arrives while this round parses and applies
         }
         const uint32_t trips = __popcll(needy) >= 32 ? rec : kParse;   // dense data: no imbalance
-        for (uint32_t np = 0; np < trips && have && qcnt < rec && can_parse(); ++np) {
-          if (kSparse || pend_lev) {   // (Code_s records always carry a level >= 1)
-            queue[qidx((uint32_t)lane, (qhead + qcnt) & (rec - 1))] =
-                (qrec_t)((pend_pos - 1u) | (pend_neg << 13) | ((pend_lev - kLevBias) << 14));
-            ++qcnt;
+        const uint32_t plim = parse_limit();
+        for (uint32_t np = 0; np < trips; ++np) {
+          const bool act = (pend_pos != kDone) & (qcnt < rec) & (bitpos < plim);
+          if (__ballot(act) == 0) break;
+          if (act) {
+            if (kSparse || pend_lev) {   // (Code_s records always carry a level >= 1)
+              queue[qidx((uint32_t)lane, (qhead + qcnt) & (rec - 1))] =
+                  (qrec_t)((pend_pos - 1u) | (pend_neg << 13) | ((pend_lev - kLevBias) << 14));
+              ++qcnt;
+            }
+            advance(pend_pos);
           }
-          advance();
         }
-        if (bad) { flag_corrupt(a.status); bad = false; }
+        if (bad) { flag_corrupt(a.status); bad = 0; }
       }
       if constexpr (KLOOP) {
         // Dense data: nearly every ring slot is due in every round, so the records are
         // applied message by message: in turn kk, lane (g2, r) takes slot r of string
         // (g2, kk), and all strings of one message run side by side.
-        uint32_t limit = wave_min_u32(have ? pend_pos - 1u : 0xFFFFFFFFu);
+        uint32_t limit = wave_min_u32(pend_pos - 1u);   // (kDone - 1: no limit from this lane)
         limit = min(limit, wend);   // 0-based positions below `limit` are due
         counts[lane] = qcnt;
         heads[lane] = qhead;
@@ -619,7 +630,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       for (uint32_t t = 0; t <= kApply; ++t)
         qv[t] = queue[((qhead + t) & (kRec - 1)) * 64u + lane];
       const uint32_t cap = qcnt > kApply ? (qv[kApply] & 0x1FFFu) : 0xFFFFFFFFu;
-      uint32_t limit = wave_min_u32(min(have ? pend_pos - 1u : 0xFFFFFFFFu, cap));
+      uint32_t limit = wave_min_u32(min(pend_pos - 1u, cap));   // (kDone - 1: no limit)
       limit = min(limit, wend);   // 0-based positions below `limit` are due
       // ---- apply the due records of this lane's own ring ---------------------------------
       // All records of one position become due in the same round.  Sums of one or
