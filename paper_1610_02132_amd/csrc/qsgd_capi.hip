@@ -302,8 +302,9 @@ int run_decode(const qsgd_params* p, const qsgd_layout* L, const void* const* ms
   // Which apply step the Elias decoder takes.  The share of nonzero levels of Q_s grows
   // like s / sqrt(d) (Lemma 3.1 (iii)); above 1/8 a string has more records per
   // 256-position window than the counting apply handles well, and Code'_s has a
-  // record for every coordinate.
-  a.kloop = (g.code == QSGD_CODE_DENSE || 64ull * g.s * g.s > g.d) ? 1u : 0u;
+  // record for every coordinate.  (The counting apply keeps a bit per message in a 32-bit
+  // word: more than 32 messages go the other way whatever the data.)
+  a.kloop = (g.code == QSGD_CODE_DENSE || 64ull * g.s * g.s > g.d || K > 32) ? 1u : 0u;
 
   {
     ScopedTiming tm("decode_check", st);

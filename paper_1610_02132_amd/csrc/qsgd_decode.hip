@@ -22,6 +22,32 @@ constexpr uint32_t kRingStride = kStrWin + 1;   // words of a lane's string ring
 
 namespace {
 
+// A piece of a string: words [idx, idx + kStrFetch), zeros at and past nwords; idx is a
+// multiple of kStrFetch.  Strings are word-aligned, so a whole piece is one 16-byte load.
+static_assert(kStrFetch == 4 && kStrWin % kStrFetch == 0, "pieces of four words");
+struct __attribute__((packed, aligned(4))) StrPiece { uint32_t w[kStrFetch]; };
+__device__ __forceinline__ void load_piece(const uint32_t* str, uint32_t idx, uint32_t nwords,
+                                           uint32_t (&t)[kStrFetch]) {
+  if (idx + kStrFetch <= nwords) {
+    const StrPiece p = *reinterpret_cast<const StrPiece*>(str + idx);
+#pragma unroll
+    for (uint32_t j = 0; j < kStrFetch; ++j) t[j] = p.w[j];
+  } else {
+#pragma unroll
+    for (uint32_t j = 0; j < kStrFetch; ++j) t[j] = idx + j < nwords ? str[idx + j] : 0u;
+  }
+}
+// Stores the piece that starts at word `idx` of the string into a lane's ring (word j of the
+// string in slot j % kStrWin; slot kStrWin mirrors slot 0).
+__device__ __forceinline__ void ring_put_piece(uint32_t* ring, uint32_t idx,
+                                               const uint32_t (&t)[kStrFetch]) {
+  const uint32_t sl = idx & (kStrWin - 1u);
+  uint32_t* const at = ring + sl;
+#pragma unroll
+  for (uint32_t j = 0; j < kStrFetch; ++j) at[j] = t[j];
+  if (sl == 0) ring[kStrWin] = t[0];
+}
+
 // Recursive Elias code (App. A.2), decoder rule unrolled: N = 1; a 0 bit outputs N,
 // a 1 bit opens an (N+1)-bit group whose value is the new N.  `w` holds the next
 // 32 stream bits, first bit on top.  G = most groups accepted (G = 1: k <= 3,
@@ -369,20 +395,10 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   uint32_t* const ring = swin + (uint32_t)lane * kRingStride;
   uint8_t* const otab = reinterpret_cast<uint8_t*>(swin + 64u * kRingStride);   // Elias table
   uint32_t sfill = 0;   // words [sfill - kStrWin, sfill) of the string are in the ring
-  auto ring_put = [&](uint32_t idx, uint32_t word) {
-    const uint32_t sl = idx & (kStrWin - 1u);
-    ring[sl] = word;
-    if (sl == 0) ring[kStrWin] = word;
-  };
   auto fetch = [&]() {
     uint32_t t[kStrFetch];
-#pragma unroll
-    for (uint32_t j = 0; j < kStrFetch; ++j) {
-      const uint32_t idx = sfill + j;
-      t[j] = idx < nwords ? str[idx] : 0u;
-    }
-#pragma unroll
-    for (uint32_t j = 0; j < kStrFetch; ++j) ring_put(sfill + j, t[j]);
+    load_piece(str, sfill, nwords, t);
+    ring_put_piece(ring, sfill, t);
     sfill += kStrFetch;
   };
   // The 32 stream bits from bit `at` on, out of the ring (bit j of the stream is bit
@@ -520,8 +536,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   bool tw_pending = false;
   auto commit_pending = [&]() {
     if (tw_pending && sfill == tw_base) {   // (a fetch on demand may have overtaken them)
-#pragma unroll
-      for (uint32_t j = 0; j < kStrFetch; ++j) ring_put(sfill + j, tw[j]);
+      ring_put_piece(ring, sfill, tw);
       sfill += kStrFetch;
     }
     tw_pending = false;
@@ -531,11 +546,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
   auto request_next = [&]() {
     tw_pending = pend_pos != kDone && sfill < nwords && sfill - (bitpos >> 5) <= kStrWin - kStrFetch;
     tw_base = sfill;
-#pragma unroll
-    for (uint32_t j = 0; j < kStrFetch; ++j) {
-      const uint32_t idx = sfill + j;
-      tw[j] = (tw_pending && idx < nwords) ? str[idx] : 0u;
-    }
+    if (tw_pending) load_piece(str, sfill, nwords, tw);
   };
   // Message-by-message apply: x is requested a whole window ahead, because its rounds
   // wait for string words at once and would wait for x with them.  Counting apply: the
@@ -633,100 +644,92 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       uint32_t limit = wave_min_u32(min(pend_pos - 1u, cap));   // (kDone - 1: no limit)
       limit = min(limit, wend);   // 0-based positions below `limit` are due
       // ---- apply the due records of this lane's own ring ---------------------------------
-      // All records of one position become due in the same round.  Sums of one or
-      // two terms do not depend on the order of the additions; only positions hit
-      // by three or more messages need the additions in message order.  The
-      // accumulator word itself first counts the position's terms:
-      //   A  every due record adds 1 to its word and learns its arrival rank;
-      //   B  the totals are read back;
-      //   C  arrival 0 stores its term (or 0.0 if the total is above two);
-      //   D  arrival 1 of a two-term position adds its term;
-      //   E  positions with more terms: messages take turns in ascending order.
-      // Every phase handles the ring entries
-      // in groups of kGrp with straight-line code: entries that do not take part
-      // add 0, or write to the lane's dump word, instead of branching, so that the
-      // LDS operations of a group are in flight together.
-      uint32_t due = 0, first = 0, two = 0, many = 0;   // bit t: ring entry t
-#pragma unroll
-      for (uint32_t t = 0; t < kApply; ++t) {
-        const uint32_t p0 = qv[t] & 0x1FFFu;
-        ad[t] = grow + ((p0 - ws) & (winp - 1u));
-        due |= (t < qcnt && p0 < limit ? 1u : 0u) << t;
-      }
-      const uint32_t tmax = 32u - (uint32_t)__clz((int)wave_max_u32(due));  // uniform
+      // All records of one position become due in the same round, and the position's word of
+      // the accumulator is 0 until then.  That word first collects WHO has a term there, a bit
+      // per message (K <= 32 on this path): a record's rank among the set bits below its own is
+      // its turn in the sum that Alg. 1's last line takes message by message.  Then
+      //   turn 0    stores its term (0 + t = t),
+      //   turn r    adds its term to what turns 0 .. r-1 left, r = 1, 2, ... while any lane
+      //             still has a record waiting: as many passes as the busiest position of
+      //             the round has terms, not one per message.
+      // Every pass handles the ring entries in groups of kGrp with straight-line code: entries
+      // that do not take part read and write the lane's dump word instead of branching, so
+      // that the LDS operations of a group are in flight together.
       constexpr uint32_t kGrp = 4;
+      {
+        uint32_t due = 0;   // bit t: ring entry t
 #pragma unroll
-      for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
-        if (t0 >= tmax) break;
-        uint32_t rk[kGrp];
-#pragma unroll
-        for (uint32_t j = 0; j < kGrp; ++j) rk[j] = atomicAdd(&accu[ad[t0 + j]], (due >> (t0 + j)) & 1u);
-#pragma unroll
-        for (uint32_t j = 0; j < kGrp; ++j) first |= (rk[j] == 0u ? 1u : 0u) << (t0 + j);
-      }
-      first &= due;
-      __syncthreads();
-#pragma unroll
-      for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
-        if (t0 >= tmax) break;
-        uint32_t c[kGrp];
-#pragma unroll
-        for (uint32_t j = 0; j < kGrp; ++j) c[j] = accu[ad[t0 + j]];
-#pragma unroll
-        for (uint32_t j = 0; j < kGrp; ++j) {
-          two |= (c[j] == 2u ? 1u : 0u) << (t0 + j);
-          many |= (c[j] > 2u ? 1u : 0u) << (t0 + j);
+        for (uint32_t t = 0; t < kApply; ++t) {
+          const uint32_t p0 = qv[t] & 0x1FFFu;
+          ad[t] = grow + ((p0 - ws) & (winp - 1u));
+          due |= ((t < qcnt) & (p0 < limit) ? 1u : 0u) << t;
         }
-      }
-      two &= due;
-      many &= due;
-      __syncthreads();
-      float term[kApply];
-#pragma unroll
-      for (uint32_t t = 0; t < kApply; ++t) {
-        const float mag = my_scale * (float)((qv[t] >> 14) + kLevBias);
-        term[t] = ((qv[t] >> 13) & 1u) ? -mag : mag;
-      }
-#pragma unroll
-      for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
-        if (t0 >= tmax) break;
-#pragma unroll
-        for (uint32_t j = 0; j < kGrp; ++j) {
-          const uint32_t t = t0 + j;
-          acc[((first >> t) & 1u) ? ad[t] : dump] = ((many >> t) & 1u) ? 0.f : term[t];
-        }
-      }
-      __syncthreads();
-      const uint32_t second = two & ~first;
-      if (__ballot(second != 0) != 0) {
+        const uint32_t tmax = 32u - (uint32_t)__clz((int)wave_max_u32(due));  // uniform
+        const uint32_t kbit = 1u << k;
 #pragma unroll
         for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
           if (t0 >= tmax) break;
-          float old[kGrp];
 #pragma unroll
           for (uint32_t j = 0; j < kGrp; ++j)
-            old[j] = acc[((second >> (t0 + j)) & 1u) ? ad[t0 + j] : dump];
-#pragma unroll
-          for (uint32_t j = 0; j < kGrp; ++j)
-            acc[((second >> (t0 + j)) & 1u) ? ad[t0 + j] : dump] = old[j] + term[t0 + j];
+            atomicOr(&accu[ad[t0 + j]], ((due >> (t0 + j)) & 1u) ? kbit : 0u);
         }
-      }
-      if (__ballot(many != 0) != 0) {
-        for (uint32_t kk = 0; kk < K; ++kk) {
-          __syncthreads();
-          if (__ballot(many != 0 && k == kk) == 0) continue;
-          if (k == kk) {
+        __syncthreads();
+        uint32_t turn[kApply / 4] = {};   // a byte per ring entry
+        static_assert(kApply % 4 == 0, "turns are packed four to a word");
 #pragma unroll
-            for (uint32_t t = 0; t < kApply; ++t)
-              if ((many >> t) & 1u) acc[ad[t]] += term[t];
+        for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
+          if (t0 >= tmax) break;
+          uint32_t who[kGrp];
+#pragma unroll
+          for (uint32_t j = 0; j < kGrp; ++j) who[j] = accu[ad[t0 + j]];
+#pragma unroll
+          for (uint32_t j = 0; j < kGrp; ++j)
+            turn[(t0 + j) / 4] |= (uint32_t)__popc(who[j] & (kbit - 1u)) << (8u * ((t0 + j) & 3u));
+        }
+        __syncthreads();
+        float term[kApply];
+#pragma unroll
+        for (uint32_t t = 0; t < kApply; ++t) {
+          const float mag = my_scale * (float)((qv[t] >> 14) + kLevBias);
+          term[t] = ((qv[t] >> 13) & 1u) ? -mag : mag;
+        }
+        uint32_t wait = due;   // entries whose turn has not come
+#pragma unroll
+        for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
+          if (t0 >= tmax) break;
+#pragma unroll
+          for (uint32_t j = 0; j < kGrp; ++j) {
+            const uint32_t t = t0 + j;
+            const bool now = ((wait >> t) & 1u) & (((turn[t / 4] >> (8u * (t & 3u))) & 0xFFu) == 0u);
+            acc[now ? ad[t] : dump] = term[t];
+            wait &= ~((now ? 1u : 0u) << t);
           }
         }
+        __syncthreads();
+        for (uint32_t r = 1; __ballot(wait != 0) != 0; ++r) {
+#pragma unroll
+          for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
+            if (t0 >= tmax) break;
+            float old[kGrp];
+            uint32_t at[kGrp];
+#pragma unroll
+            for (uint32_t j = 0; j < kGrp; ++j) {
+              const uint32_t t = t0 + j;
+              const bool now = ((wait >> t) & 1u) & (((turn[t / 4] >> (8u * (t & 3u))) & 0xFFu) == r);
+              at[j] = now ? ad[t] : dump;
+              wait &= ~((now ? 1u : 0u) << t);
+              old[j] = acc[at[j]];
+            }
+#pragma unroll
+            for (uint32_t j = 0; j < kGrp; ++j) acc[at[j]] = old[j] + term[t0 + j];
+          }
+          __syncthreads();
+        }
+        const uint32_t ndue = (uint32_t)__popc(due);
+        qhead = (qhead + ndue) & (kRec - 1);
+        qcnt -= ndue;
+        if (limit == wend) break;   // uniform: every string is parsed past this window
       }
-      __syncthreads();
-      const uint32_t ndue = (uint32_t)__popc(due);
-      qhead = (qhead + ndue) & (kRec - 1);
-      qcnt -= ndue;
-      if (limit == wend) break;   // uniform: every string is parsed past this window
     }
     // ---- string words requested a window ago arrive; request the next ones ---------------
     commit_pending();
@@ -786,7 +789,8 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
 }
 
 template <int CODE, int LG, int NQ, bool KLOOP, bool Q16>
-__global__ __launch_bounds__(64) void k_decode_elias(DecodeArgs a) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NQ == 4 && !KLOOP ? QSGD_DEC_WAVES : 1)))
+void k_decode_elias(DecodeArgs a) {
   if (*a.status != 0) return;
   extern __shared__ uint32_t smem[];
   // LDS: [acc: gw*winp floats][record rings][string rings: 64*kRingStride][Elias table: 32][dump 64]
@@ -883,20 +887,10 @@ __global__ __launch_bounds__(64) void k_decode_tile(DecodeArgs a) {
   // of a pair), and the odd stride keeps the lanes on distinct banks.
   uint32_t* const ring = swin + (uint32_t)lane * kRingStride;
   uint32_t sfill = 0;   // words [sfill - kStrWin, sfill) of the string are in the ring
-  auto ring_put = [&](uint32_t idx, uint32_t word) {
-    const uint32_t sl = idx & (kStrWin - 1u);
-    ring[sl] = word;
-    if (sl == 0) ring[kStrWin] = word;
-  };
   auto fetch = [&]() {
     uint32_t t[kStrFetch];
-#pragma unroll
-    for (uint32_t j = 0; j < kStrFetch; ++j) {
-      const uint32_t idx = sfill + j;
-      t[j] = idx < nwords ? str[idx] : 0u;
-    }
-#pragma unroll
-    for (uint32_t j = 0; j < kStrFetch; ++j) ring_put(sfill + j, t[j]);
+    load_piece(str, sfill, nwords, t);
+    ring_put_piece(ring, sfill, t);
     sfill += kStrFetch;
   };
   // The 32 stream bits from bit `at` on, out of the ring (bit j of the stream is bit
@@ -977,8 +971,7 @@ __global__ __launch_bounds__(64) void k_decode_tile(DecodeArgs a) {
   for (uint32_t j = 0; j < kStrFetch; ++j) tw[j] = 0u;
   auto commit_pending = [&]() {
     if (tw_pending && sfill - (bp >> 5) <= kStrWin - kStrFetch) {
-#pragma unroll
-      for (uint32_t j = 0; j < kStrFetch; ++j) ring_put(sfill + j, tw[j]);
+      ring_put_piece(ring, sfill, tw);
       sfill += kStrFetch;
       tw_pending = false;
     }
@@ -986,11 +979,7 @@ __global__ __launch_bounds__(64) void k_decode_tile(DecodeArgs a) {
   auto request_next = [&]() {
     if (!tw_pending && pend_pos != kDone && sfill < nwords) {
       tw_pending = true;
-#pragma unroll
-      for (uint32_t j = 0; j < kStrFetch; ++j) {
-        const uint32_t idx = sfill + j;
-        tw[j] = idx < nwords ? str[idx] : 0u;
-      }
+      load_piece(str, sfill, nwords, tw);
     }
   };
 

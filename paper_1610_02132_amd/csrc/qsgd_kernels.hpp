@@ -19,6 +19,11 @@ constexpr uint32_t kMaxTeams = 8192;       // most teams (regions) one encode us
 #ifndef QSGD_ENC_WAVES
 #define QSGD_ENC_WAVES 6
 #endif
+// Ring decoder of the Elias codes: waves per SIMD its registers are budgeted for (LDS lets a
+// compute unit hold twenty of its one-wavefront workgroups on the workload it is tuned on).
+#ifndef QSGD_DEC_WAVES
+#define QSGD_DEC_WAVES 5
+#endif
 #ifndef QSGD_ENC_WAVES_LIST
 #define QSGD_ENC_WAVES_LIST 5
 #endif
