@@ -657,25 +657,31 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       // that the LDS operations of a group are in flight together.
       constexpr uint32_t kGrp = 4;
       {
-        uint32_t due = 0;   // bit t: ring entry t
+        // (positions ascend along a string, so the due entries are the first `ndue` of the ring)
+        bool due[kApply];
+        uint32_t ndue = 0;
 #pragma unroll
         for (uint32_t t = 0; t < kApply; ++t) {
           const uint32_t p0 = qv[t] & 0x1FFFu;
           ad[t] = grow + ((p0 - ws) & (winp - 1u));
-          due |= ((t < qcnt) & (p0 < limit) ? 1u : 0u) << t;
+          due[t] = (t < qcnt) & (p0 < limit);
+          ndue += due[t] ? 1u : 0u;
         }
-        const uint32_t tmax = 32u - (uint32_t)__clz((int)wave_max_u32(due));  // uniform
+        const uint32_t tmax = wave_max_u32(ndue);  // uniform: ring entries any lane applies
         const uint32_t kbit = 1u << k;
 #pragma unroll
         for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
           if (t0 >= tmax) break;
 #pragma unroll
-          for (uint32_t j = 0; j < kGrp; ++j)
-            atomicOr(&accu[ad[t0 + j]], ((due >> (t0 + j)) & 1u) ? kbit : 0u);
+          for (uint32_t j = 0; j < kGrp; ++j) atomicOr(&accu[ad[t0 + j]], due[t0 + j] ? kbit : 0u);
         }
         __syncthreads();
-        uint32_t turn[kApply / 4] = {};   // a byte per ring entry
+        // a byte per ring entry: its turn, 0xFF for an entry that is not due
+        uint32_t turn[kApply / 4];
         static_assert(kApply % 4 == 0, "turns are packed four to a word");
+#pragma unroll
+        for (uint32_t t = 0; t < kApply / 4; ++t) turn[t] = 0xFFFFFFFFu;
+        uint32_t last = 0;   // the highest turn of this lane's entries
 #pragma unroll
         for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
           if (t0 >= tmax) break;
@@ -683,8 +689,13 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
 #pragma unroll
           for (uint32_t j = 0; j < kGrp; ++j) who[j] = accu[ad[t0 + j]];
 #pragma unroll
-          for (uint32_t j = 0; j < kGrp; ++j)
-            turn[(t0 + j) / 4] |= (uint32_t)__popc(who[j] & (kbit - 1u)) << (8u * ((t0 + j) & 3u));
+          for (uint32_t j = 0; j < kGrp; ++j) {
+            const uint32_t t = t0 + j;
+            const uint32_t mine = (uint32_t)__popc(who[j] & (kbit - 1u));
+            const uint32_t sh = 8u * (t & 3u);
+            turn[t / 4] = due[t] ? (turn[t / 4] & ~(0xFFu << sh)) | (mine << sh) : turn[t / 4];
+            last = due[t] ? max(last, mine) : last;
+          }
         }
         __syncthreads();
         float term[kApply];
@@ -693,20 +704,19 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
           const float mag = my_scale * (float)((qv[t] >> 14) + kLevBias);
           term[t] = ((qv[t] >> 13) & 1u) ? -mag : mag;
         }
-        uint32_t wait = due;   // entries whose turn has not come
 #pragma unroll
         for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
           if (t0 >= tmax) break;
 #pragma unroll
           for (uint32_t j = 0; j < kGrp; ++j) {
             const uint32_t t = t0 + j;
-            const bool now = ((wait >> t) & 1u) & (((turn[t / 4] >> (8u * (t & 3u))) & 0xFFu) == 0u);
+            const bool now = ((turn[t / 4] >> (8u * (t & 3u))) & 0xFFu) == 0u;
             acc[now ? ad[t] : dump] = term[t];
-            wait &= ~((now ? 1u : 0u) << t);
           }
         }
         __syncthreads();
-        for (uint32_t r = 1; __ballot(wait != 0) != 0; ++r) {
+        const uint32_t rmax = wave_max_u32(last);   // uniform
+        for (uint32_t r = 1; r <= rmax; ++r) {
 #pragma unroll
           for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
             if (t0 >= tmax) break;
@@ -715,9 +725,8 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
 #pragma unroll
             for (uint32_t j = 0; j < kGrp; ++j) {
               const uint32_t t = t0 + j;
-              const bool now = ((wait >> t) & 1u) & (((turn[t / 4] >> (8u * (t & 3u))) & 0xFFu) == r);
+              const bool now = ((turn[t / 4] >> (8u * (t & 3u))) & 0xFFu) == r;
               at[j] = now ? ad[t] : dump;
-              wait &= ~((now ? 1u : 0u) << t);
               old[j] = acc[at[j]];
             }
 #pragma unroll
@@ -725,7 +734,6 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
           }
           __syncthreads();
         }
-        const uint32_t ndue = (uint32_t)__popc(due);
         qhead = (qhead + ndue) & (kRec - 1);
         qcnt -= ndue;
         if (limit == wend) break;   // uniform: every string is parsed past this window
