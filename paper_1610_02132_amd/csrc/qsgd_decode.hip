@@ -425,6 +425,16 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
     len = after + more + 1u;
     return (1u << more) | rest;
   };
+  // The code words of 1 .. 4 ("0", "100", "110", "101000") from their first three bits, for
+  // s <= 4: nibble b of the two constants is the value and the length for the top bits b
+  // ("111" would be a value of 8 or more, and "101" has to go on with "000").  No table
+  // look-up, that is one LDS round trip less in the chain from one record to the next.
+  auto omega_small = [&](uint32_t w, uint32_t& len, uint32_t& open_end) -> uint32_t {
+    const uint32_t six = w >> 26, b = six >> 3;
+    len = (0x03631111u >> (4u * b)) & 0xFu;
+    open_end = ((b == 7u) | ((b == 5u) & (six != 0x28u))) ? 0x80000000u : 0u;
+    return (0x03421111u >> (4u * b)) & 0xFu;
+  };
   // A record reads at most the two words at bitpos / 32 (kNarrow) or one more, so a lane may
   // parse while bitpos is below this limit (none once the whole string is in the ring: past
   // its end the ring may hold anything, those bits lie behind endbit).
@@ -443,7 +453,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       const uint32_t gap = omega_tab(w, gl, e1);
       if (!kNarrow) w = peek(bitpos + gl); else w <<= gl;
       pend_neg = w >> 31;
-      const uint32_t lev = omega_tab(w << 1, ll, e2);
+      const uint32_t lev = Q16 ? omega_small(w << 1, ll, e2) : omega_tab(w << 1, ll, e2);
       bitpos += gl + 1u + ll;
       pos += gap;
       pend_lev = lev;
