@@ -98,7 +98,10 @@ __device__ __forceinline__ void draw4_uniform_hi(uint64_t gidx, uint32_t hi, con
 template <int CPW, bool ALIGNED>
 __device__ __forceinline__ void draw_all(uint64_t gidx0, int lane, const QuantCtx& q,
                                          uint32_t (&r)[CPW][4]) {
-  // blocks drawn side by side: the largest of 8, 4, 2 that divides CPW
+  // blocks drawn side by side, the largest of 8, 4, 2 that divides CPW: the round keys are
+  // stepped once for all of them (the compiler still sinks each block's rounds into the
+  // chunk that uses it; pinning them together, for more independent multiplies in flight,
+  // measured 2% slower: the vector unit, not the chain, is what the draws wait for)
   constexpr int kWish = QSGD_PHILOX_TOGETHER;
   constexpr int kTogether = CPW % kWish == 0 ? kWish : (CPW % 4 == 0 && kWish > 4 ? 4 : (CPW % 2 == 0 && kWish > 1 ? 2 : 1));
   if constexpr (ALIGNED && kTogether > 1) {
@@ -267,37 +270,42 @@ __device__ __forceinline__ bool encode_sparse_list(const float4 (&v)[CPW],
       nz[j] = u < fabsf(ts[j]);
       mk[j] = __ballot(nz[j]);
     }
-    const uint32_t cnt = (uint32_t)(__popcll(mk[0]) + __popcll(mk[1]) + __popcll(mk[2]) +
-                                    __popcll(mk[3]));
-    const uint64_t m01 = mk[0] | mk[1], m23 = mk[2] | mk[3];
-    if (cnt == 0 || count + cnt > LIST) {
-      // nothing to list, or no room
-    } else if (((mk[0] & mk[1]) | (mk[2] & mk[3]) | (m01 & m23)) == 0) {
-      // the usual case on sparse data, no lane with two survivors: the lanes below count
-      // once each, and one slot serves whichever of the lane's values survived
-      uint32_t* const at = list + count + bits_below(m01 | m23);
+    const uint64_t m01 = mk[0] | mk[1], m23 = mk[2] | mk[3], any = m01 | m23;
+    if (((mk[0] & mk[1]) | (mk[2] & mk[3]) | (m01 & m23)) == 0) {
+      // the usual case on sparse data, no lane with two survivors: the survivors are the
+      // lanes of `any`, the lanes below count once each, and one slot serves whichever of
+      // the lane's values survived
+      const uint32_t cnt = (uint32_t)__popcll(any);
+      if (cnt != 0 && count + cnt <= LIST) {   // (else nothing to list, or no room)
+        uint32_t* const at = list + count + bits_below(any);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (nz[j]) {
-          at[0] = p1 + (uint32_t)(c * kChunk + j);
-          at[LIST] = __float_as_uint(ts[j]);
-          at[2 * LIST] = r[j];
+        for (int j = 0; j < 4; ++j) {
+          if (nz[j]) {
+            at[0] = p1 + (uint32_t)(c * kChunk + j);
+            at[LIST] = __float_as_uint(ts[j]);
+            at[2 * LIST] = r[j];
+          }
         }
       }
+      count += cnt;
     } else {
-      uint32_t* at = list + count + bits_below(mk[0]) + bits_below(mk[1]) + bits_below(mk[2]) +
-                     bits_below(mk[3]);
+      const uint32_t cnt = (uint32_t)(__popcll(mk[0]) + __popcll(mk[1]) + __popcll(mk[2]) +
+                                      __popcll(mk[3]));
+      if (count + cnt <= LIST) {
+        uint32_t* at = list + count + bits_below(mk[0]) + bits_below(mk[1]) +
+                       bits_below(mk[2]) + bits_below(mk[3]);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (nz[j]) {
-          at[0] = p1 + (uint32_t)(c * kChunk + j);
-          at[LIST] = __float_as_uint(ts[j]);
-          at[2 * LIST] = r[j];
-          ++at;
+        for (int j = 0; j < 4; ++j) {
+          if (nz[j]) {
+            at[0] = p1 + (uint32_t)(c * kChunk + j);
+            at[LIST] = __float_as_uint(ts[j]);
+            at[2 * LIST] = r[j];
+            ++at;
+          }
         }
       }
+      count += cnt;
     }
-    count += cnt;
   }
   __builtin_amdgcn_wave_barrier();
   if (count == 0) return false;
