@@ -198,7 +198,7 @@ void plan_encode(const Geometry& g, uint32_t teams_target, uint64_t ws_avail, En
   const size_t ring_words =
       g.code == QSGD_CODE_SPARSE ? qsgd::ring_words(pl.ring ? pl.ring : qsgd::kRing) : 0;
   pl.lds = 4 * ((size_t)pl.dst_words + (size_t)pl.tw * (pl.sub_words + ring_words)) + 8 * pl.tw +
-           16 * pl.tw + 16 + (pl.ring ? 4 * qsgd::kOmegaTab : 0);
+           16 * pl.tw + 16 + (g.code == QSGD_CODE_SPARSE ? 4 * qsgd::kOmegaTab : 0);
 }
 
 // ---- optional kernel timing -----------------------------------------------------

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(64 * TW)
   uint32_t* const ring_all = sub_all + TW * a.sub_words;
   double* const red = reinterpret_cast<double*>(ring_all + TW * kRingW);
   WaveOut* const winfo = reinterpret_cast<WaveOut*>(red + TW);
-  uint32_t* const otab = reinterpret_cast<uint32_t*>(winfo + TW);  // kOmegaTab words if LIST
+  uint32_t* const otab = reinterpret_cast<uint32_t*>(winfo + TW);  // kOmegaTab words (Code_s)
 
   const int tid = threadIdx.x;
   // (the wavefront's number is the same in all its lanes: as a scalar, what depends on it --
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(64 * TW)
   uint32_t* const ring = ring_all + wave * kRingW;
 
   for (uint32_t j = tid; j < a.dst_words + TW * a.sub_words; j += 64 * TW) smem[j] = 0;
-  if (LIST) {
+  if (CODE == QSGD_CODE_SPARSE) {
     for (uint32_t k = tid; k < kOmegaTab; k += 64 * TW) {
       uint64_t code = 0; uint32_t len = 0;
       if (k) omega_encode(k, code, len);
@@ -260,7 +260,8 @@ __global__ __launch_bounds__(64 * TW)
           gave_up = encode_sparse_list<CPW, LIST>(v, rall, nchunks, wstart, lane, qc, ring, otab,
                                                   sub, wo);
         } else {
-          (void)encode_sparse_wave<CPW, false>(v, rall, nchunks, wstart, lane, qc, ring, sub, wo);
+          (void)encode_sparse_wave<CPW, false>(v, rall, nchunks, wstart, lane, qc, ring, otab, sub,
+                                               wo);
         }
         if (LIST && gave_up) {
           // dense data after all: clear what the sub-stream holds and code the wavefront's

@@ -122,35 +122,51 @@ __device__ __forceinline__ void draw_all(uint64_t gidx0, int lane, const QuantCt
   }
 }
 
-// Stage 2 on `take` (1..64) records starting at ring slot `head`.
+// Codes up to 64 records, one per lane (`live`: this lane has one), and appends them to the
+// sub-stream at bit `bits`; returns the bits after them.
+//   gap   position minus the position of the record before (0: the sub-stream's first record,
+//         whose gap whoever joins the sub-streams adds)
+//   tsb   bits of t with the sign of the value,  word  the draw word
+//   otab  Elias code words of 1 .. kOmegaTab - 1 as (code << 8) | length in LDS, or null
+// When every gap and level of the batch is in the table a record's whole code fits 32 bits
+// (at most 14 + 1 + 14); otherwise the code words are computed (64-bit arithmetic).
 // WIDE: gaps may need more than 21 bits, emit gap and (sign, level) separately.
-template <bool WIDE, uint32_t RING = kRing>
-__device__ __forceinline__ void sparse_flush(const uint32_t* ring, uint32_t head, uint32_t take,
-                                             int lane, const QuantCtx& q, uint32_t* sub,
-                                             WaveOut& out) {
-  const uint32_t idx = (head + (uint32_t)lane) & (RING - 1);
-  const bool live = (uint32_t)lane < take;
-  uint32_t pos = 0, len = 0, gl = 0, cl = 0;
+template <bool WIDE>
+__device__ __forceinline__ uint32_t code_batch(bool live, uint32_t gap, uint32_t tsb,
+                                               uint32_t word, int lane, const QuantCtx& q,
+                                               const uint32_t* otab, uint32_t* sub,
+                                               uint32_t bits) {
+  const uint32_t z = live ? min(quantize_scaled(__uint_as_float(tsb), word), q.s) : 0u;
+  gap = live ? gap : 0u;
+  if (!WIDE && otab != nullptr && __ballot(max(z, gap) >= kOmegaTab) == 0) {
+    const uint32_t ez = otab[z], eg = otab[gap];
+    const uint32_t ll = ez & 0xFFu, gl = eg & 0xFFu;
+    const uint32_t cl = live ? ll + 1u : 0u;
+    const uint32_t cw = ((tsb >> 31) << ll) | (ez >> 8);
+    const uint32_t code = ((eg >> 8) << cl) | cw;
+    const uint32_t len = gl + cl;
+    const uint32_t incl = wave_incl_scan_u32(len, lane);
+    const uint32_t off = bits + incl - len;
+    if (live) {
+      const uint32_t top = code << (32u - len);
+      const uint32_t w = off >> 5, sh = off & 31u;
+      atomicOr(&sub[w], top >> sh);
+      if (sh + len > 32u) atomicOr(&sub[w + 1], top << (32u - sh));
+    }
+    return bits + lane_bcast(incl, 63);
+  }
   uint64_t gc = 0, cw = 0;
+  uint32_t gl = 0, cl = 0;
   if (live) {
-    pos = ring[idx];
-    const float ts = __uint_as_float(ring[RING + idx]);
-    const uint32_t word = ring[2 * RING + idx];
-    const uint32_t prev = lane == 0 ? out.last_pos : ring[(idx - 1u) & (RING - 1)];
-    const float t = fabsf(ts);
-    const float fl = floorf(t);
-    const float p = t - fl;
-    const float u = (float)(word >> 8) * (1.0f / 16777216.0f);
-    const uint32_t z = (fl >= q.s_f) ? q.s : (uint32_t)fl + ((u < p) ? 1u : 0u);
     uint64_t lc; uint32_t ll;
     omega_encode(z, lc, ll);
-    cw = ((uint64_t)(ts < 0.f ? 1u : 0u) << ll) | lc;
+    cw = ((uint64_t)(tsb >> 31) << ll) | lc;
     cl = ll + 1u;
-    if (prev != 0) omega_encode(pos - prev, gc, gl);
-    len = gl + cl;
+    if (gap) omega_encode(gap, gc, gl);
   }
+  const uint32_t len = gl + cl;
   const uint32_t incl = wave_incl_scan_u32(len, lane);
-  const uint32_t off = out.bits + incl - len;
+  const uint32_t off = bits + incl - len;
   if (live) {
     if (WIDE) {
       if (gl) lds_emit(sub, off, gc, gl);
@@ -159,7 +175,25 @@ __device__ __forceinline__ void sparse_flush(const uint32_t* ring, uint32_t head
       lds_emit(sub, off, (gc << cl) | cw, len);
     }
   }
-  out.bits += lane_bcast(incl, 63);
+  return bits + lane_bcast(incl, 63);
+}
+
+// Stage 2 on `take` (1..64) records starting at ring slot `head`.
+template <bool WIDE, uint32_t RING = kRing>
+__device__ __forceinline__ void sparse_flush(const uint32_t* ring, uint32_t head, uint32_t take,
+                                             int lane, const QuantCtx& q, const uint32_t* otab,
+                                             uint32_t* sub, WaveOut& out) {
+  const uint32_t idx = (head + (uint32_t)lane) & (RING - 1);
+  const bool live = (uint32_t)lane < take;
+  uint32_t pos = 0, gap = 0, tsb = 0, word = 0;
+  if (live) {
+    pos = ring[idx];
+    tsb = ring[RING + idx];
+    word = ring[2 * RING + idx];
+    const uint32_t prev = lane == 0 ? out.last_pos : ring[(idx - 1u) & (RING - 1)];
+    gap = prev ? pos - prev : 0u;
+  }
+  out.bits = code_batch<WIDE>(live, gap, tsb, word, lane, q, otab, sub, out.bits);
   if (out.first_pos == 0) out.first_pos = lane_bcast(pos, 0);
   out.last_pos = lane_bcast(pos, (int)take - 1);
 }
@@ -170,6 +204,7 @@ __device__ __forceinline__ void sparse_flush(const uint32_t* ring, uint32_t head
 //   pos0      bucket position (0-based) of the wavefront's first value
 //   rall      draw words of every chunk (draw_all)
 //   ring      kRingWords words of LDS private to this wavefront
+//   otab      table of Elias code words in LDS (code_batch), or null
 //   sub       zero-initialised LDS words private to this wavefront
 // Returns true when it gave up (RING < 256 only): the sub-stream and `out` then hold
 // leftovers and the caller starts over with encode_sparse_direct.
@@ -178,7 +213,8 @@ __device__ __forceinline__ bool encode_sparse_wave(const float4 (&v)[CPW],
                                                    const uint32_t (&rall)[CPW][4], int nchunks,
                                                    uint32_t pos0, int lane,
                                                    const QuantCtx& q, uint32_t* ring,
-                                                   uint32_t* sub, WaveOut& out) {
+                                                   const uint32_t* otab, uint32_t* sub,
+                                                   WaveOut& out) {
   uint32_t head = 0, count = 0;
 #pragma unroll
   for (int c = 0; c < CPW; ++c) {
@@ -199,7 +235,7 @@ __device__ __forceinline__ bool encode_sparse_wave(const float4 (&v)[CPW],
     if constexpr (RING >= 256) {
       while (count + cnt > RING) {  // make room (only in very dense data)
         const uint32_t take = min(64u, count);
-        sparse_flush<WIDE, RING>(ring, head, take, lane, q, sub, out);
+        sparse_flush<WIDE, RING>(ring, head, take, lane, q, otab, sub, out);
         head += take;
         count -= take;
       }
@@ -223,7 +259,7 @@ __device__ __forceinline__ bool encode_sparse_wave(const float4 (&v)[CPW],
     count += cnt;
     __builtin_amdgcn_wave_barrier();
     while (count >= 64u) {
-      sparse_flush<WIDE, RING>(ring, head, 64u, lane, q, sub, out);
+      sparse_flush<WIDE, RING>(ring, head, 64u, lane, q, otab, sub, out);
       head += 64u;
       count -= 64u;
     }
@@ -231,7 +267,7 @@ __device__ __forceinline__ bool encode_sparse_wave(const float4 (&v)[CPW],
   __builtin_amdgcn_wave_barrier();
   while (count > 0) {
     const uint32_t take = min(64u, count);
-    sparse_flush<WIDE, RING>(ring, head, take, lane, q, sub, out);
+    sparse_flush<WIDE, RING>(ring, head, take, lane, q, otab, sub, out);
     head += take;
     count -= take;
   }
@@ -314,49 +350,14 @@ __device__ __forceinline__ bool encode_sparse_list(const float4 (&v)[CPW],
   for (uint32_t head = 0; head < count; head += kWave) {
     const uint32_t i = head + (uint32_t)lane;
     const bool live = i < count;
-    uint32_t z = 0, gap = 0, tsb = 0;
+    uint32_t gap = 0, tsb = 0, word = 0;
     if (live) {
       const uint32_t pos = list[i];
       tsb = list[LIST + i];
-      const uint32_t word = list[2 * LIST + i];
-      const uint32_t prev = i ? list[i - 1u] : 0u;
-      z = min(quantize_scaled(__uint_as_float(tsb), word), q.s);
-      gap = prev ? pos - prev : 0u;
+      word = list[2 * LIST + i];
+      gap = i ? pos - list[i - 1u] : 0u;
     }
-    uint32_t len;
-    if (__ballot(max(z, gap) >= kOmegaTab) == 0) {
-      // every code word of the batch from the table: a record is at most 14 + 1 + 14 bits
-      const uint32_t ez = otab[z], eg = otab[gap];
-      const uint32_t ll = ez & 0xFFu, gl = eg & 0xFFu;
-      const uint32_t cl = live ? ll + 1u : 0u;
-      const uint32_t cw = ((tsb >> 31) << ll) | (ez >> 8);
-      const uint32_t code = ((eg >> 8) << cl) | cw;
-      len = gl + cl;
-      const uint32_t incl = wave_incl_scan_u32(len, lane);
-      const uint32_t off = bits + incl - len;
-      if (live) {
-        const uint32_t top = code << (32u - len);
-        const uint32_t w = off >> 5, sh = off & 31u;
-        atomicOr(&sub[w], top >> sh);
-        if (sh + len > 32u) atomicOr(&sub[w + 1], top << (32u - sh));
-      }
-      bits += lane_bcast(incl, 63);
-    } else {
-      uint64_t gc = 0, cw = 0;
-      uint32_t gl = 0, cl = 0;
-      if (live) {
-        uint64_t lc; uint32_t ll;
-        omega_encode(z, lc, ll);
-        cw = ((uint64_t)(tsb >> 31) << ll) | lc;
-        cl = ll + 1u;
-        if (gap) omega_encode(gap, gc, gl);
-      }
-      len = gl + cl;
-      const uint32_t incl = wave_incl_scan_u32(len, lane);
-      const uint32_t off = bits + incl - len;
-      if (live) lds_emit(sub, off, (gc << cl) | cw, len);
-      bits += lane_bcast(incl, 63);
-    }
+    bits = code_batch<false>(live, gap, tsb, word, lane, q, otab, sub, bits);
   }
   out.bits = bits;
   out.first_pos = __builtin_amdgcn_readfirstlane(list[0]);

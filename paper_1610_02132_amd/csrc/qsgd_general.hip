@@ -211,7 +211,7 @@ __global__ __launch_bounds__(64) void k_gen_encode(GenArgs a) {
     uint32_t rall[kSegChunks][4];
     draw_all<kSegChunks, ALIGNED>(a.index_base + r.gidx0, lane, qc, rall);
     if (CODE == QSGD_CODE_SPARSE) {
-      encode_sparse_wave<kSegChunks, true>(v, rall, nchunks, r.pos0, lane, qc, ring, sub, wo);
+      encode_sparse_wave<kSegChunks, true>(v, rall, nchunks, r.pos0, lane, qc, ring, nullptr, sub, wo);
     } else if (CODE == QSGD_CODE_DENSE) {
       encode_dense_wave<kSegChunks>(v, rall, nchunks, r.len, lane, qc, sub, wo);
     } else {
