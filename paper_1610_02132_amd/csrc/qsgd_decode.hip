@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256) void k_decode_fixed(DecodeArgs a) {
       }
       if (!my_ok) { flag_corrupt(a.status); my_scale = 0.f; my_esc = 0xFFFFFFFFu; }
     }
-    const uint64_t okmask = __ballot(my_ok != 0);
+    const uint64_t okmask = __builtin_amdgcn_ballot_w64(my_ok != 0);
     // every message is intact and every chunk of the group is complete: no per-load tests
     const bool whole = okmask == all_ok && m % (CH * kChunk) == 0;
     for (uint32_t g0 = 0; g0 < m; g0 += CH * kChunk) {
@@ -584,8 +584,8 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
       // A parse pass costs as many trips of the divergent loop as its busiest lane
       // takes, so passes are short and start when most lanes can use all the trips
       // (their rings have room), or when a lane is out of records for this window.
-      const uint64_t needy = __ballot(pend_pos <= wend);
-      const uint32_t nroom = (uint32_t)__popcll(__ballot(pend_pos != kDone && qcnt + kRoom <= rec));
+      const uint64_t needy = __builtin_amdgcn_ballot_w64(pend_pos <= wend);
+      const uint32_t nroom = (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(pend_pos != kDone && qcnt + kRoom <= rec));
       if (needy != 0 || nroom >= kParseLanes) {
         // top up the string rings together, then parse
         commit_pending();
@@ -598,8 +598,13 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
         const uint32_t trips = __popcll(needy) >= 32 ? rec : kParse;   // dense data: no imbalance
         const uint32_t plim = parse_limit();
         for (uint32_t np = 0; np < trips; ++np) {
-          const bool act = (pend_pos != kDone) & (qcnt < rec) & (bitpos < plim);
-          if (__ballot(act) == 0) break;
+          const bool c1 = pend_pos != kDone, c2 = qcnt < rec, c3 = bitpos < plim;
+          const bool act = c1 & c2 & c3;
+          // (the wavefront's vote from the three comparisons' own masks: a vote on their
+          // conjunction first turns it into a register and compares again)
+          if ((__builtin_amdgcn_ballot_w64(c1) & __builtin_amdgcn_ballot_w64(c2) &
+               __builtin_amdgcn_ballot_w64(c3)) == 0)
+            break;
           if (act) {
             if (kSparse || pend_lev) {   // (Code_s records always carry a level >= 1)
               queue[qidx((uint32_t)lane, (qhead + qcnt) & (rec - 1))] =
@@ -1043,15 +1048,18 @@ __global__ __launch_bounds__(64) void k_decode_tile(DecodeArgs a) {
     for (;;) {
       const uint32_t plim = parse_limit();
       for (uint32_t t = 0; t < kTileBatch; ++t) {
-        const bool act = pend_pos <= wend && bp < plim;
-        if (__ballot(act) == 0) break;
+        const bool c1 = pend_pos <= wend, c2 = bp < plim;
+        const bool act = c1 & c2;
+        // (the wavefront's vote from the two comparisons' own masks: a vote on their
+        // conjunction first turns it into a register and compares again)
+        if ((__builtin_amdgcn_ballot_w64(c1) & __builtin_amdgcn_ballot_w64(c2)) == 0) break;
         if (act) {
           if (kSparse || pend_lev)
             row[pend_pos - 1u - ws] = (int8_t)(pend_neg ? -(int)pend_lev : (int)pend_lev);
           advance(pend_pos);
         }
       }
-      if (__ballot(pend_pos <= wend) == 0) break;
+      if (__builtin_amdgcn_ballot_w64(pend_pos <= wend) == 0) break;
       commit_pending();
       request_next();
     }
