@@ -176,6 +176,32 @@ def test_dense_chunks_inside_sparse_buckets(s, d):
     assert check_step(P0, msgs_dev, msgs_host, 0.1, x, 3) == 0
 
 
+def test_survivor_list_overflow_takes_the_direct_coder():
+    """s = 5, d = 8192 is coded through the survivor list (Lemma 3.1 (iii) promises it half
+    full), a list of 256 records per wavefront.  Buckets whose mass lies evenly on one
+    wavefront's 2048 values bring s sqrt(2048) = 226 survivors there in expectation, a few
+    of them more than 256: the oracle's levels say which (at least one with these seeds),
+    and those wavefronts must start over with the direct coder, same bits."""
+    s, d, nb = 5, 8192, 400
+    n = nb * d
+    gen = torch.Generator().manual_seed(99)
+    g = torch.zeros(n)
+    for b in range(nb):
+        w0 = 2048 * (b % 4)
+        mag = 0.95 + 0.1 * torch.rand(2048, generator=gen)
+        sign = torch.where(torch.rand(2048, generator=gen) < 0.5, -1.0, 1.0)
+        g[b * d + w0: b * d + w0 + 2048] = mag * sign
+    P = q.Params(n=n, s=s, d=d, code=q.CODE_SPARSE, seed=5, stream_id=2, iteration=7)
+    lev = qo.quantize(oracle_params(P), g.numpy())["levels"].reshape(nb, 4, 2048)
+    per_wave = (lev != 0).sum(axis=2).max(axis=1)
+    assert (per_wave > 256).sum() >= 1 and (per_wave <= 256).sum() >= 1
+    status, words, msg = Device(P).encode(g.cuda())
+    assert status == 0
+    assert compare_encode(P, g.numpy(), words) == 0
+    x = np.linspace(-1, 1, n, dtype=np.float32)
+    assert check_step(P, [msg], [words], 0.1, x, 1) == 0
+
+
 @pytest.mark.parametrize("same_gradient", [False, True])
 @pytest.mark.parametrize("nb", [1, 3])
 def test_long_sparse_buckets_read_all_messages_at_once(same_gradient, nb):
