@@ -44,8 +44,7 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 }
 
 // N blocks at once (counter words 0 and 1 per block, words 2 and 3 and the key shared): each
-// round's key is stepped once for all of them, and a wavefront has 2 N independent
-// multiplies in flight instead of two.
+// round's key is stepped once for all of them.
 template <int N>
 __device__ __forceinline__ void philox4x32_10_xn(const uint32_t (&c0)[N], const uint32_t (&c1)[N],
                                                  uint32_t c2, uint32_t c3, uint32_t k0,
