@@ -682,11 +682,16 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
           due[t] = (t < qcnt) & (p0 < limit);
           ndue += due[t] ? 1u : 0u;
         }
-        const uint32_t tmax = wave_max_u32(ndue);  // uniform: ring entries any lane applies
+        // uniform: does any lane apply an entry of the group that starts at t0?  (a vote per
+        // group costs a comparison; the wavefront's maximum would cost a dozen shuffles)
+        bool grp[kApply / kGrp];
+#pragma unroll
+        for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp)
+          grp[t0 / kGrp] = __builtin_amdgcn_ballot_w64(ndue > t0) != 0;
         const uint32_t kbit = 1u << k;
 #pragma unroll
         for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
-          if (t0 >= tmax) break;
+          if (!grp[t0 / kGrp]) break;
 #pragma unroll
           for (uint32_t j = 0; j < kGrp; ++j) atomicOr(&accu[ad[t0 + j]], due[t0 + j] ? kbit : 0u);
         }
@@ -699,7 +704,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
         uint32_t last = 0;   // the highest turn of this lane's entries
 #pragma unroll
         for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
-          if (t0 >= tmax) break;
+          if (!grp[t0 / kGrp]) break;
           uint32_t who[kGrp];
 #pragma unroll
           for (uint32_t j = 0; j < kGrp; ++j) who[j] = accu[ad[t0 + j]];
@@ -721,7 +726,7 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
         }
 #pragma unroll
         for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
-          if (t0 >= tmax) break;
+          if (!grp[t0 / kGrp]) break;
 #pragma unroll
           for (uint32_t j = 0; j < kGrp; ++j) {
             const uint32_t t = t0 + j;
@@ -730,11 +735,10 @@ __device__ __forceinline__ void decode_elias_body(const DecodeArgs& a, float* ac
           }
         }
         __syncthreads();
-        const uint32_t rmax = wave_max_u32(last);   // uniform
-        for (uint32_t r = 1; r <= rmax; ++r) {
+        for (uint32_t r = 1; __builtin_amdgcn_ballot_w64(last >= r) != 0; ++r) {
 #pragma unroll
           for (uint32_t t0 = 0; t0 < kApply; t0 += kGrp) {
-            if (t0 >= tmax) break;
+            if (!grp[t0 / kGrp]) break;
             float old[kGrp];
             uint32_t at[kGrp];
 #pragma unroll
